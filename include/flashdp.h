@@ -1,0 +1,143 @@
+/*
+ * flashdp.h - C ABI of the MI355X (gfx950) per-layer DP weight-gradient library.
+ *
+ * One call computes, for a linear layer Y = X W^T with activations X[B][T][d_in] and
+ * output gradients dY[B][T][d_out] (row-major, last index contiguous), the clipped and
+ * noised weight gradient of per-layer DP-SGD:
+ *
+ *     G_i      = dY_i^T X_i                      per-sample gradient, [d_out][d_in]
+ *     n_i      = ||G_i||_F                       per-sample, per-layer norm
+ *     c_i      = 1 / max(1, n_i / C)             clip factor
+ *     out_grad = sum_i c_i G_i + sigma * C * z   z ~ N(0, I), counter-based
+ *
+ * Paper: Algorithm 1 "FlashDP with Block-wise All-Reduce" (tile contraction, intra/inter
+ * block norm reduction, synchronisation, clip, noise + batch aggregation, store) and
+ * Appendix B.2 (the explicit four-stage flow it is equivalent to).  The batch is summed,
+ * not averaged (Algorithm 1, aggregation step); the caller divides by B if it wants the
+ * mean of Appendix A.1.
+ *
+ * Noise: the paper names no generator.  z is a stateless field
+ *     z[e] = BoxMuller(Philox4x32-10(key = (seed & 0xffffffff, seed >> 32),
+ *                                    counter = (g & 0xffffffff, g >> 32, layer, 0)))[e & 3],
+ *     e = d * d_in + p,  g = e >> 2,
+ * uniforms u(r) = ((r >> 8) + 0.5) * 2^-24, pairs (r0,r1) -> (z0,z1) = rho*(cos,sin)(2 pi u(r1)),
+ * rho = sqrt(-2 ln u(r0)), and (r2,r3) -> (z2,z3) likewise.  Same (seed, layer) => same noise:
+ * the caller must fold the training step into seed, or noise repeats across steps.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HIP, current device) owned by the caller.
+ *     flashdp_layer_t arrays and scalar arguments are HOST memory.
+ *   - Calls enqueue work on a HIP stream and return without synchronising it.  Device
+ *     faults surface at the caller's next synchronisation.
+ *   - out_grad and out_norms are overwritten, never accumulated into.
+ *   - Inputs are read-only.  X pointers of different layers may alias.
+ *   - dtype: FLASHDP_BF16 / FLASHDP_F16 / FLASHDP_F32 is the storage type of X and dY; products are
+ *     accumulated in fp32; out_grad and out_norms are fp32.
+ *   - Pointers must be 16-byte aligned.  Any positive B, T, d_in, d_out is accepted; the
+ *     matrix-core path needs d_in and d_out to be multiples of 8 (16-bit types), other shapes
+ *     take a slower generic kernel.
+ *   - NaN/Inf in the inputs propagate to out_norms / out_grad.
+ *   - Return value: FLASHDP_OK (0) or a negative flashdp_status; on error nothing is enqueued.
+ */
+#ifndef FLASHDP_H
+#define FLASHDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum flashdp_status {
+  FLASHDP_OK = 0,
+  FLASHDP_INVALID_ARGUMENT = -1,   /* null pointer, dim <= 0, C <= 0 or not finite, sigma < 0 or not finite, bad enum */
+  FLASHDP_MISALIGNED = -2,         /* a data pointer or the workspace is not 16-byte aligned */
+  FLASHDP_UNSUPPORTED_SHAPE = -3,  /* a dimension or byte count exceeds what the kernels index (2^31 elements per sample tensor) */
+  FLASHDP_WORKSPACE_TOO_SMALL = -4,
+  FLASHDP_NO_DEVICE = -5,          /* no HIP device visible */
+  FLASHDP_HIP_ERROR = -6           /* allocation or launch failure reported by the runtime */
+} flashdp_status;
+
+enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
+
+/* How the grid-wide dependency of Algorithm 1 (the clip factor needs every tile of G_i;
+ * Section 4.2 "Adaptive Kernel Implementation") is resolved:
+ *   TWOPASS  norm pass, then a second contraction that accumulates c_i G_i (each G_i computed twice;
+ *            workspace: a few KB);
+ *   SCRATCH  each G_i tile is computed once, its square-sum taken from the fp32 accumulators, the tile
+ *            parked in a per-layer scratch (16-bit for 16-bit inputs, fp32 for fp32 inputs), and a
+ *            streaming kernel forms sum_i c_i G_i + noise (workspace: B * d_out * d_in elements);
+ *   AUTO     SCRATCH when the workspace is large enough, else TWOPASS.                                 */
+enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2 };
+
+/* One linear layer of a block (Appendix A.1, "Per-Layer Gradient Processing": every layer is clipped
+ * by its own norm with its own C and sigma). */
+typedef struct flashdp_layer {
+  const void* X;      /* device, [B][T][d_in],  dtype */
+  const void* dY;     /* device, [B][T][d_out], dtype */
+  int64_t d_in;       /* P */
+  int64_t d_out;      /* D */
+  float C;            /* clipping threshold, > 0 */
+  float sigma;        /* noise multiplier, >= 0; 0 adds no noise and generates none */
+  uint64_t seed;      /* Philox key */
+  uint32_t layer;     /* Philox counter word 2 */
+  float* out_grad;    /* device, [d_out][d_in] fp32, overwritten */
+  float* out_norms;   /* device, [B] fp32, pre-clip n_i, overwritten; may be NULL */
+} flashdp_layer_t;
+
+/* Algorithm 1 for one layer with the calling thread's context (stream, dtype, layer index, schedule,
+ * workspace; see the setters below; defaults: null stream, bf16, layer 0, AUTO, library-owned workspace).
+ * When no workspace has been set the library allocates one with hipMalloc on first use and keeps it
+ * (grow-only, per device) until flashdp_release(); allocation may synchronise the device. */
+int flashdp_linear_dp_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                           float C, float sigma, uint64_t seed, float* out_grad, float* out_norms);
+
+/* Per-block multi-layer variant: Algorithm 1 for each of n_layers layers (same B and T), enqueued in
+ * order on `stream` (a hipStream_t, may be NULL).  `workspace` is caller-owned device memory of at least
+ * flashdp_workspace_bytes(...) bytes, reused layer after layer; with workspace == NULL and
+ * schedule == TWOPASS or AUTO the library-owned workspace is used as above.  Calls that share a
+ * workspace must be ordered on one stream. */
+int flashdp_block_dp_grad(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                          int schedule, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace the given schedule needs for these layers (the maximum over layers).  Returns 0 on
+ * invalid arguments. */
+size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                               int schedule);
+
+/* Non-private weight gradient out_grad = sum_i dY_i^T X_i (Appendix B.1, Eq. "batched-grad") computed by
+ * the same contraction kernel with the norm, clip and noise steps switched off: the comparator the DP
+ * path is timed against, and the C -> infinity, sigma = 0 special case. */
+int flashdp_plain_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                       int dtype, float* out_grad, void* stream);
+
+/* Fills z[0..n) (device, fp32) with the noise field of (seed, layer): the field that out_grad receives
+ * scaled by sigma*C.  For checking the generator on its own. */
+int flashdp_noise_field(uint64_t seed, uint32_t layer, int64_t n, float* z, void* stream);
+
+/* z[4g + j] = j-th normal made from words[4g .. 4g+3] by the Box-Muller map above (device pointers,
+ * n_groups groups of four 32-bit words).  For checking the uniform -> normal map at words a keyed field
+ * reaches only by chance (extreme uniforms, quadrant boundaries). */
+int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* stream);
+
+/* Thread-local context used by flashdp_linear_dp_grad. */
+int flashdp_set_stream(void* hip_stream);
+int flashdp_set_workspace(void* device_ptr, size_t bytes);   /* NULL, 0: back to the library-owned one */
+int flashdp_set_dtype(int dtype);
+int flashdp_set_layer(uint32_t layer);
+int flashdp_set_schedule(int schedule);
+
+/* Frees the library-owned workspaces (synchronises the device first). */
+int flashdp_release(void);
+
+/* Name of the schedule the last call on this thread used: "twopass" or "scratch" ("none" before any). */
+const char* flashdp_last_schedule(void);
+
+const char* flashdp_status_string(int status);
+int flashdp_version(void);   /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHDP_H */

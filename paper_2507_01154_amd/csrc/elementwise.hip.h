@@ -1,0 +1,159 @@
+// The memory-bound steps of Algorithm 1 after the grid-wide synchronisation: inter-block reduction of the
+// squared norms and clip factor (B_G' = B_G / max(1, sqrt(||B_G||^2') / C)), and the batch aggregation with
+// noise (B_dW = sum_b B_G' + N(0, sigma^2 C^2 I)) read back from the per-layer scratch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_mfma.hip.h"
+#include "philox_gauss.h"
+
+namespace flashdp {
+
+// One workgroup per sample: sums that sample's per-tile partial squared norms in a fixed order (fp64, so
+// the result does not depend on scheduling), then n_i = sqrt(.), c_i = 1 / max(1, n_i / C).
+// Replaces the per-block atomic add of the paper's inter-block reduce; the kernel boundary before it is
+// the block-wise synchronisation.
+__global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restrict__ partials, int tiles, float C,
+                                                           float* __restrict__ factors, float* __restrict__ out_norms) {
+  __shared__ double red[256];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  double s = 0.0;
+  for (int k = tid; k < tiles; k += 256) s += (double)partials[(size_t)i * tiles + k];
+  red[tid] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) red[tid] += red[tid + w];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const double n = sqrt(red[0]);
+    const double ratio = n / (double)C;
+    factors[i] = (float)(1.0 / (ratio > 1.0 ? ratio : 1.0));
+    if (out_norms) out_norms[i] = (float)n;
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void widen8(const u32x4_t v, float* f) {
+  if constexpr (DT == DT_BF16) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f[2 * q] = __builtin_bit_cast(float, v[q] << 16);
+      f[2 * q + 1] = __builtin_bit_cast(float, v[q] & 0xFFFF0000u);
+    }
+  } else {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f[2 * q] = (float)__builtin_bit_cast(_Float16, (unsigned short)(v[q] & 0xFFFFu));
+      f[2 * q + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(v[q] >> 16));
+    }
+  }
+}
+
+// out[e] = sum_i c_i * scratch[i][e] + noise_scale * z[e], 8 consecutive elements per thread
+// (16-byte loads from the 16-bit scratch, two Philox groups, two 16-byte stores).  n8 = S / 8.
+template <int DT>
+__global__ __launch_bounds__(256) void aggregate16_kernel(const void* __restrict__ scratch, const float* __restrict__ factors,
+                                                          int B, size_t S, size_t n8, float noise_scale, uint64_t seed,
+                                                          uint32_t layer, float* __restrict__ out) {
+  const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= n8) return;
+  float acc[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
+  const u32x4_t* src = (const u32x4_t*)scratch + v;
+  const size_t stride = S / 8;
+  for (int i = 0; i < B; ++i) {
+    const u32x4_t raw = __builtin_nontemporal_load(src + (size_t)i * stride);
+    const float c = factors[i];
+    float f[8];
+    widen8<DT>(raw, f);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = fmaf(c, f[q], acc[q]);
+  }
+  if (noise_scale != 0.0f) {
+    const Normals4 z0 = noise_group(seed, layer, 2 * v), z1 = noise_group(seed, layer, 2 * v + 1);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      acc[q] = fmaf(noise_scale, z0.z[q], acc[q]);
+      acc[4 + q] = fmaf(noise_scale, z1.z[q], acc[4 + q]);
+    }
+  }
+  float4* dst = (float4*)out + 2 * v;
+  dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+}
+
+// Generic version: any scratch type, any S; one Philox group (4 elements) per thread.
+template <int DT>
+__global__ __launch_bounds__(256) void aggregate_generic_kernel(const void* __restrict__ scratch, const float* __restrict__ factors,
+                                                                int B, size_t S, float noise_scale, uint64_t seed,
+                                                                uint32_t layer, float* __restrict__ out) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (4 * g >= S) return;
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int i = 0; i < B; ++i) {
+    const float c = factors[i];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const size_t e = 4 * g + q;
+      if (e < S) {
+        float val;
+        if constexpr (DT == DT_F32) {
+          val = ((const float*)scratch)[(size_t)i * S + e];
+        } else if constexpr (DT == DT_BF16) {
+          val = __builtin_bit_cast(float, (uint32_t)((const unsigned short*)scratch)[(size_t)i * S + e] << 16);
+        } else {
+          val = (float)((const _Float16*)scratch)[(size_t)i * S + e];
+        }
+        acc[q] = fmaf(c, val, acc[q]);
+      }
+    }
+  }
+  if (noise_scale != 0.0f) {
+    const Normals4 z = noise_group(seed, layer, g);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = fmaf(noise_scale, z.z[q], acc[q]);
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (4 * g + q < S) out[4 * g + q] = acc[q];
+}
+
+// out[e] = (ADD ? out[e] : 0) + scale * z[e]: the noise step alone (second pass of the two-pass schedule,
+// and the stand-alone field for checks).
+template <bool ADD>
+__global__ __launch_bounds__(256) void noise_kernel(float* __restrict__ out, size_t S, float scale, uint64_t seed, uint32_t layer) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (4 * g >= S) return;
+  const Normals4 z = noise_group(seed, layer, g);
+  if (4 * g + 3 < S && (((uintptr_t)out) & 15) == 0) {
+    float4* p = (float4*)out + g;
+    float4 v = ADD ? *p : make_float4(0.f, 0.f, 0.f, 0.f);
+    v.x = fmaf(scale, z.z[0], v.x);
+    v.y = fmaf(scale, z.z[1], v.y);
+    v.z = fmaf(scale, z.z[2], v.z);
+    v.w = fmaf(scale, z.z[3], v.w);
+    *p = v;
+  } else {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (4 * g + q < S) out[4 * g + q] = fmaf(scale, z.z[q], ADD ? out[4 * g + q] : 0.0f);
+  }
+}
+
+// z = BoxMuller(words): the uniform -> normal map on caller-supplied words, for checking edge cases
+// (extreme uniforms, quadrant boundaries) that a keyed field reaches only by chance.
+__global__ __launch_bounds__(256) void box_muller_kernel(const uint32_t* __restrict__ words, size_t n_groups, float* __restrict__ z) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= n_groups) return;
+  Words4 w;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) w.w[q] = words[4 * g + q];
+  const Normals4 o = box_muller4(w);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) z[4 * g + q] = o.z[q];
+}
+
+}  // namespace flashdp

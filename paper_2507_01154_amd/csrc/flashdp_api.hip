@@ -1,0 +1,423 @@
+// C ABI and host-side dispatch of the per-layer DP weight-gradient library (see include/flashdp.h).
+// Host code only validates, sizes the workspace, picks kernels and enqueues them; every step of
+// Algorithm 1 runs in the kernels.
+#include "../../include/flashdp.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <mutex>
+
+#include "elementwise.hip.h"
+#include "gemm_mfma.hip.h"
+#include "gemm_simple.hip.h"
+
+using namespace flashdp;
+
+namespace {
+
+struct Context {
+  hipStream_t stream = nullptr;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  int dtype = FLASHDP_BF16;
+  uint32_t layer = 0;
+  int schedule = FLASHDP_SCHEDULE_AUTO;
+  const char* last_schedule = "none";
+};
+thread_local Context g_ctx;
+
+struct OwnedWs { void* ptr = nullptr; size_t bytes = 0; };
+std::mutex g_ws_mutex;
+std::map<int, OwnedWs> g_owned;   // device -> library-owned workspace
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool valid_dtype(int d) { return d == FLASHDP_BF16 || d == FLASHDP_F32 || d == FLASHDP_F16; }
+inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_SCRATCH; }
+inline size_t elt_bytes(int dtype) { return dtype == FLASHDP_F32 ? 4 : 2; }
+
+// ---- kernel plans --------------------------------------------------------------------------------
+
+using Cfg256x4 = TileCfg<256, 256, 64, 2, 2>;   // 4 waves, 128x128 per wave
+using Cfg256x8 = TileCfg<256, 256, 64, 2, 4>;   // 8 waves, 128x64 per wave
+using Cfg128x4 = TileCfg<128, 128, 64, 2, 2>;   // 4 waves, 64x64 per wave
+
+enum Path { PATH_SIMPLE = 0, PATH_256x4 = 1, PATH_256x8 = 2, PATH_128x4 = 3 };
+
+struct Plan {
+  Path path;
+  int bm, bn;
+  int tiles_m, tiles_n;
+};
+
+int env_int(const char* name, int dflt) {
+  const char* s = std::getenv(name);
+  return (s && *s) ? std::atoi(s) : dflt;
+}
+
+Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
+  Plan p;
+  const bool mfma_ok = dtype != FLASHDP_F32 && P % 8 == 0 && D % 8 == 0 &&
+                       (T + 64) * (P > D ? P : D) * 2 < (int64_t(1) << 31);
+  if (!mfma_ok) {
+    p.path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
+  } else {
+    int choice = env_int("FLASHDP_TILE", 0);
+    if (choice == 0) {
+      // enough 256x256 work items to fill 256 CUs a few times over, else the smaller tile
+      const int64_t items = ((D + 255) / 256) * ((P + 255) / 256) * B;
+      choice = items >= 1024 ? PATH_256x4 : PATH_128x4;
+    }
+    p.path = (Path)choice;
+    p.bm = p.bn = (p.path == PATH_128x4) ? 128 : 256;
+  }
+  p.tiles_m = (int)((D + p.bm - 1) / p.bm);
+  p.tiles_n = (int)((P + p.bn - 1) / p.bn);
+  return p;
+}
+
+struct WsLayout { size_t factors, partials, scratch, total; };
+
+WsLayout ws_layout(const Plan& p, int64_t B, int64_t P, int64_t D, int dtype, bool with_scratch) {
+  WsLayout w;
+  w.factors = 0;
+  w.partials = align_up((size_t)B * 4, 256);
+  w.scratch = w.partials + align_up((size_t)B * p.tiles_m * p.tiles_n * 4, 256);
+  w.total = w.scratch + (with_scratch ? align_up((size_t)B * D * P * elt_bytes(dtype), 256) : 0);
+  return w;
+}
+
+template <typename Cfg, int MODE, int DT>
+hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
+  static bool attr_set = false;   // one attribute call per instantiation (idempotent, race-benign)
+  auto kern = gemm_mfma_kernel<Cfg, MODE, DT>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = a.tiles_m * a.tiles_n;
+  const int grid = (MODE == MODE_ACCUM) ? tiles : tiles * a.B;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, a);
+  return hipGetLastError();
+}
+
+template <int MODE, int DT>
+hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& a, hipStream_t st) {
+  if constexpr (DT != DT_F32) {
+    switch (p.path) {
+      case PATH_256x4: return launch_mfma<Cfg256x4, MODE, DT>(a, st);
+      case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
+      case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
+      default: break;
+    }
+  }
+  const int tiles = a.tiles_m * a.tiles_n;
+  const int grid = (MODE == MODE_ACCUM) ? tiles : tiles * a.B;
+  hipLaunchKernelGGL((gemm_simple_kernel<MODE, DT>), dim3(grid), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_gemm(const Plan& p, int dtype, const GemmArgs& a, hipStream_t st) {
+  switch (dtype) {
+    case FLASHDP_BF16: return launch_gemm_dt<MODE, DT_BF16>(p, a, st);
+    case FLASHDP_F16: return launch_gemm_dt<MODE, DT_F16>(p, a, st);
+    default: return launch_gemm_dt<MODE, DT_F32>(p, a, st);
+  }
+}
+
+hipError_t launch_aggregate(int dtype, const void* scratch, const float* factors, int B, size_t S, float noise_scale,
+                            uint64_t seed, uint32_t layer, float* out, hipStream_t st) {
+  if (dtype != FLASHDP_F32 && S % 8 == 0) {
+    const size_t n8 = S / 8;
+    const unsigned grid = (unsigned)((n8 + 255) / 256);
+    if (dtype == FLASHDP_BF16)
+      hipLaunchKernelGGL((aggregate16_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out);
+    else
+      hipLaunchKernelGGL((aggregate16_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out);
+  } else {
+    const size_t groups = (S + 3) / 4;
+    const unsigned grid = (unsigned)((groups + 255) / 256);
+    if (dtype == FLASHDP_BF16)
+      hipLaunchKernelGGL((aggregate_generic_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out);
+    else if (dtype == FLASHDP_F16)
+      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out);
+    else
+      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F32>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out);
+  }
+  return hipGetLastError();
+}
+
+// ---- validation ----------------------------------------------------------------------------------
+
+int check_dims(int64_t B, int64_t T, int64_t P, int64_t D) {
+  if (B <= 0 || T <= 0 || P <= 0 || D <= 0) return FLASHDP_INVALID_ARGUMENT;
+  const int64_t lim = int64_t(1) << 31;
+  if (B >= (1 << 20) || T >= lim || P >= lim || D >= lim) return FLASHDP_UNSUPPORTED_SHAPE;
+  if (T * P >= lim || T * D >= lim) return FLASHDP_UNSUPPORTED_SHAPE;   // per-sample tensors are indexed with 32 bits
+  const int64_t tiles = ((D + 63) / 64) * ((P + 63) / 64);
+  if (tiles * B >= lim) return FLASHDP_UNSUPPORTED_SHAPE;              // grid size
+  return FLASHDP_OK;
+}
+
+int check_layer(const flashdp_layer_t& L, int64_t B, int64_t T) {
+  if (!L.X || !L.dY || !L.out_grad) return FLASHDP_INVALID_ARGUMENT;
+  if (!(L.C > 0.0f) || !std::isfinite(L.C)) return FLASHDP_INVALID_ARGUMENT;
+  if (!(L.sigma >= 0.0f) || !std::isfinite(L.sigma)) return FLASHDP_INVALID_ARGUMENT;
+  int st = check_dims(B, T, L.d_in, L.d_out);
+  if (st != FLASHDP_OK) return st;
+  if (!aligned16(L.X) || !aligned16(L.dY) || !aligned16(L.out_grad) || (L.out_norms && (reinterpret_cast<uintptr_t>(L.out_norms) & 3u)))
+    return FLASHDP_MISALIGNED;
+  return FLASHDP_OK;
+}
+
+int device_or_error(int* dev) {
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) { (void)hipGetLastError(); return FLASHDP_NO_DEVICE; }
+  if (hipGetDevice(dev) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_NO_DEVICE; }
+  return FLASHDP_OK;
+}
+
+int owned_workspace(size_t need, void** ptr, size_t* bytes) {
+  int dev = 0;
+  int st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  OwnedWs& w = g_owned[dev];
+  if (w.bytes < need) {
+    if (w.ptr) {
+      if (hipDeviceSynchronize() != hipSuccess) return FLASHDP_HIP_ERROR;   // earlier calls may still use it
+      (void)hipFree(w.ptr);
+      w.ptr = nullptr; w.bytes = 0;
+    }
+    void* p = nullptr;
+    if (hipMalloc(&p, need) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; }
+    w.ptr = p; w.bytes = need;
+  }
+  *ptr = w.ptr; *bytes = w.bytes;
+  return FLASHDP_OK;
+}
+
+int resolve_schedule(int schedule) {
+  const char* s = std::getenv("FLASHDP_SCHEDULE");
+  if (s && *s) {
+    if (!std::strcmp(s, "twopass")) return FLASHDP_SCHEDULE_TWOPASS;
+    if (!std::strcmp(s, "scratch")) return FLASHDP_SCHEDULE_SCRATCH;
+  }
+  return schedule;
+}
+
+size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool with_scratch) {
+  const Plan p = make_plan(B, T, L.d_in, L.d_out, dtype);
+  return ws_layout(p, B, L.d_in, L.d_out, dtype, with_scratch).total;
+}
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; } } while (0)
+
+// Enqueues Algorithm 1 for one layer.
+int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool use_scratch, char* ws, hipStream_t st) {
+  const int64_t P = L.d_in, D = L.d_out;
+  const Plan plan = make_plan(B, T, P, D, dtype);
+  const WsLayout wl = ws_layout(plan, B, P, D, dtype, use_scratch);
+  GemmArgs a;
+  a.X = L.X; a.dY = L.dY;
+  a.B = (int)B; a.T = (int)T; a.P = (int)P; a.D = (int)D;
+  a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
+  a.partials = reinterpret_cast<float*>(ws + wl.partials);
+  a.scratch = use_scratch ? (void*)(ws + wl.scratch) : nullptr;
+  float* factors = reinterpret_cast<float*>(ws + wl.factors);
+  a.factors = factors;
+  a.out = L.out_grad;
+  const int tiles = plan.tiles_m * plan.tiles_n;
+  const size_t S = (size_t)D * P;
+  const float noise_scale = L.sigma * L.C;
+
+  if (use_scratch) {
+    HIP_TRY(launch_gemm<MODE_SPILL>(plan, dtype, a, st));
+    hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, st));
+  } else {
+    HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
+    hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, st));
+    if (noise_scale != 0.0f) {
+      const size_t groups = (S + 3) / 4;
+      hipLaunchKernelGGL((noise_kernel<true>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, L.out_grad, S, noise_scale, L.seed, L.layer);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+  return FLASHDP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int flashdp_block_dp_grad(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                          int schedule, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!layers || n_layers <= 0 || !valid_dtype(dtype) || !valid_schedule(schedule)) return FLASHDP_INVALID_ARGUMENT;
+  for (int l = 0; l < n_layers; ++l) {
+    int st = check_layer(layers[l], B, T);
+    if (st != FLASHDP_OK) return st;
+  }
+  if (workspace && !aligned16(workspace)) return FLASHDP_MISALIGNED;
+  schedule = resolve_schedule(schedule);
+  size_t need_scratch = 0, need_small = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    need_scratch = std::max(need_scratch, layer_ws_bytes(layers[l], B, T, dtype, true));
+    need_small = std::max(need_small, layer_ws_bytes(layers[l], B, T, dtype, false));
+  }
+  int dev = 0;
+  int st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  char* ws = static_cast<char*>(workspace);
+  bool use_scratch;
+  if (workspace) {
+    if (schedule == FLASHDP_SCHEDULE_SCRATCH) {
+      if (workspace_bytes < need_scratch) return FLASHDP_WORKSPACE_TOO_SMALL;
+      use_scratch = true;
+    } else if (schedule == FLASHDP_SCHEDULE_TWOPASS) {
+      if (workspace_bytes < need_small) return FLASHDP_WORKSPACE_TOO_SMALL;
+      use_scratch = false;
+    } else {
+      use_scratch = workspace_bytes >= need_scratch;
+      if (!use_scratch && workspace_bytes < need_small) return FLASHDP_WORKSPACE_TOO_SMALL;
+    }
+  } else {
+    use_scratch = schedule != FLASHDP_SCHEDULE_TWOPASS;
+    void* p = nullptr; size_t got = 0;
+    st = owned_workspace(use_scratch ? need_scratch : need_small, &p, &got);
+    if (st != FLASHDP_OK) return st;
+    ws = static_cast<char*>(p);
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    st = run_layer(layers[l], B, T, dtype, use_scratch, ws, static_cast<hipStream_t>(stream));
+    if (st != FLASHDP_OK) return st;
+  }
+  g_ctx.last_schedule = use_scratch ? "scratch" : "twopass";
+  return FLASHDP_OK;
+}
+
+int flashdp_linear_dp_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                           float C, float sigma, uint64_t seed, float* out_grad, float* out_norms) {
+  flashdp_layer_t L;
+  L.X = X; L.dY = dY; L.d_in = d_in; L.d_out = d_out; L.C = C; L.sigma = sigma; L.seed = seed;
+  L.layer = g_ctx.layer; L.out_grad = out_grad; L.out_norms = out_norms;
+  return flashdp_block_dp_grad(&L, 1, B, T, g_ctx.dtype, g_ctx.schedule, g_ctx.ws, g_ctx.ws_bytes, g_ctx.stream);
+}
+
+size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype, int schedule) {
+  if (!layers || n_layers <= 0 || !valid_dtype(dtype) || !valid_schedule(schedule)) return 0;
+  size_t need = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (check_dims(B, T, layers[l].d_in, layers[l].d_out) != FLASHDP_OK) return 0;
+    need = std::max(need, layer_ws_bytes(layers[l], B, T, dtype, schedule != FLASHDP_SCHEDULE_TWOPASS));
+  }
+  return need;
+}
+
+int flashdp_plain_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                       int dtype, float* out_grad, void* stream) {
+  if (!X || !dY || !out_grad || !valid_dtype(dtype)) return FLASHDP_INVALID_ARGUMENT;
+  int st = check_dims(B, T, d_in, d_out);
+  if (st != FLASHDP_OK) return st;
+  if (!aligned16(X) || !aligned16(dY) || !aligned16(out_grad)) return FLASHDP_MISALIGNED;
+  int dev = 0;
+  st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  const Plan plan = make_plan(B, T, d_in, d_out, dtype);
+  GemmArgs a;
+  a.X = X; a.dY = dY; a.B = (int)B; a.T = (int)T; a.P = (int)d_in; a.D = (int)d_out;
+  a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
+  a.partials = nullptr; a.scratch = nullptr; a.factors = nullptr; a.out = out_grad;
+  HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, static_cast<hipStream_t>(stream)));
+  return FLASHDP_OK;
+}
+
+int flashdp_noise_field(uint64_t seed, uint32_t layer, int64_t n, float* z, void* stream) {
+  if (!z || n <= 0) return FLASHDP_INVALID_ARGUMENT;
+  if (reinterpret_cast<uintptr_t>(z) & 3u) return FLASHDP_MISALIGNED;
+  int dev = 0;
+  int st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  const size_t groups = ((size_t)n + 3) / 4;
+  if (groups / 256 >= (size_t(1) << 31)) return FLASHDP_UNSUPPORTED_SHAPE;
+  hipLaunchKernelGGL((noise_kernel<false>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream), z, (size_t)n, 1.0f, seed, layer);
+  HIP_TRY(hipGetLastError());
+  return FLASHDP_OK;
+}
+
+int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* stream) {
+  if (!words || !z || n_groups <= 0) return FLASHDP_INVALID_ARGUMENT;
+  int dev = 0;
+  int st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  hipLaunchKernelGGL(box_muller_kernel, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream), words, (size_t)n_groups, z);
+  HIP_TRY(hipGetLastError());
+  return FLASHDP_OK;
+}
+
+int flashdp_set_stream(void* hip_stream) { g_ctx.stream = static_cast<hipStream_t>(hip_stream); return FLASHDP_OK; }
+
+int flashdp_set_workspace(void* device_ptr, size_t bytes) {
+  if ((device_ptr == nullptr) != (bytes == 0)) return FLASHDP_INVALID_ARGUMENT;
+  if (device_ptr && !aligned16(device_ptr)) return FLASHDP_MISALIGNED;
+  g_ctx.ws = device_ptr; g_ctx.ws_bytes = bytes;
+  return FLASHDP_OK;
+}
+
+int flashdp_set_dtype(int dtype) {
+  if (!valid_dtype(dtype)) return FLASHDP_INVALID_ARGUMENT;
+  g_ctx.dtype = dtype;
+  return FLASHDP_OK;
+}
+
+int flashdp_set_layer(uint32_t layer) { g_ctx.layer = layer; return FLASHDP_OK; }
+
+int flashdp_set_schedule(int schedule) {
+  if (!valid_schedule(schedule)) return FLASHDP_INVALID_ARGUMENT;
+  g_ctx.schedule = schedule;
+  return FLASHDP_OK;
+}
+
+int flashdp_release(void) {
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  int cur = 0;
+  const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+  for (auto& kv : g_owned) {
+    if (!kv.second.ptr) continue;
+    if (hipSetDevice(kv.first) != hipSuccess) continue;
+    (void)hipDeviceSynchronize();
+    (void)hipFree(kv.second.ptr);
+    kv.second = OwnedWs();
+  }
+  if (have_cur) (void)hipSetDevice(cur);
+  (void)hipGetLastError();
+  return FLASHDP_OK;
+}
+
+const char* flashdp_last_schedule(void) { return g_ctx.last_schedule; }
+
+const char* flashdp_status_string(int status) {
+  switch (status) {
+    case FLASHDP_OK: return "ok";
+    case FLASHDP_INVALID_ARGUMENT: return "invalid argument";
+    case FLASHDP_MISALIGNED: return "pointer not 16-byte aligned";
+    case FLASHDP_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case FLASHDP_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case FLASHDP_NO_DEVICE: return "no HIP device";
+    case FLASHDP_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int flashdp_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,286 @@
+// Per-sample weight-gradient contraction on the gfx950 matrix cores.
+//
+// Steps of Algorithm 1 covered here: load tiles of dY and X from HBM to on-chip memory, compute the
+// per-sample gradient tile B_G = sum_T B_dY^T B_X, and the intra-block reduction of its squared norm
+// (one scalar per workgroup).  Depending on MODE the tile is then dropped (norm pass), parked in the
+// 16-bit scratch (single-compute schedule), or - with the clip factors already known - accumulated
+// over the batch as sum_i c_i G_i (second pass; with c == 1 this is the non-private Eq. "batched-grad").
+//
+// Operand layout.  out[m][n] = sum_t dY[t][m] * X[t][n]: both operands have the reduction index t as the
+// slow dimension and m (= d_out) resp. n (= d_in) contiguous.  Tiles are copied to LDS as they are
+// (rows = t), 16 bytes per lane and coalesced along m / n.  The matrix-core operand wants, per lane,
+// eight consecutive t for one m; the LDS transpose read ds_read_b64_tr_b16 delivers exactly that from
+// the t-major tile: within 16 lanes, lane s supplies the address of 4 contiguous 16-bit values and lane
+// i receives element (i % 4) of lanes (i / 4), (i / 4) + 4, (i / 4) + 8, (i / 4) + 12.  So lane s points
+// at row (s / 4), column 4 * (s % 4) of a 4 (t) x 16 (m) block and lane i gets column i for 4 rows.
+//
+// v_mfma_f32_32x32x16 (bf16 or f16): lane l holds A[m = l % 32][k = 8 * (l / 32) + 0..7], likewise B with
+// n = l % 32; accumulator register j of lane l is C[row = 8 * (j / 4) + 4 * (l / 32) + (j % 4)][col = l % 32].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace flashdp {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+enum : int { MODE_NORM = 0, MODE_SPILL = 1, MODE_ACCUM = 2 };
+enum : int { DT_BF16 = 0, DT_F32 = 1, DT_F16 = 2 };
+
+struct GemmArgs {
+  const void* X;         // [B][T][P]
+  const void* dY;        // [B][T][D]
+  int B, T, P, D;
+  int tiles_m, tiles_n;  // ceil(D / BM), ceil(P / BN)
+  float* partials;       // [B][tiles_m * tiles_n] squared-norm partial sums (NORM, SPILL)
+  void* scratch;         // [B][D][P] 16-bit (SPILL)
+  const float* factors;  // [B] clip factors (ACCUM); nullptr = all ones
+  float* out;            // [D][P] (ACCUM)
+};
+
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
+struct TileCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int NT = 64 * WAVES_M * WAVES_N;
+  static constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;   // per-wave tile
+  static constexpr int FM = TM / 32, FN = TN / 32;             // 32x32 blocks per wave
+  static constexpr int PAD = 32;                               // row stride = 64 bytes mod 256: 4 consecutive rows hit 4 bank windows
+  static constexpr int LDA = BM + PAD, LDB = BN + PAD;         // LDS row strides in elements
+  static constexpr int A_STAGE = BK * LDA, B_STAGE = BK * LDB; // elements per stage
+  static constexpr int LDS_BYTES = 2 * (A_STAGE + B_STAGE) * 2;
+  static constexpr int CA = BK * BM / 8 / NT, CB = BK * BN / 8 / NT;   // 16-byte chunks per thread per k-tile
+  static_assert(BK % 16 == 0 && TM % 32 == 0 && TN % 32 == 0, "tile shape");
+  static_assert((BK * BM / 8) % NT == 0 && (BK * BN / 8) % NT == 0, "copy shape");
+  static_assert(NT % (BM / 8) == 0 && NT % (BN / 8) == 0, "copy rows");
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+template <int DT>
+__device__ __forceinline__ f32x16_t mfma32(const s16x8_t a, const s16x8_t b, const f32x16_t c) {
+  if constexpr (DT == DT_BF16) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  }
+}
+
+__device__ __forceinline__ s16x4_t lds_read_tr(const unsigned short* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
+}
+
+template <int DT>
+__device__ __forceinline__ unsigned short to_16bit(float v) {
+  if constexpr (DT == DT_BF16) {
+    return __builtin_bit_cast(unsigned short, (__bf16)v);
+  } else {
+    return __builtin_bit_cast(unsigned short, (_Float16)v);
+  }
+}
+
+// Workgroup id -> logical work item, so that the workgroups resident on one XCD (ids congruent mod 8)
+// cover a contiguous range of work items and share operand panels in that XCD's L2.
+__device__ __forceinline__ int xcd_remap(int bid, int total) {
+  const int per = total >> 3, rem = total & 7;
+  const int xcd = bid & 7, idx = bid >> 3;
+  return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+}
+
+// Tiles are walked in bands of GROUP_M tile rows, column by column inside a band, so that consecutive
+// work items reuse the same dY panel (rows) and neighbouring X panels.
+template <int GROUP_M>
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int* tm, int* tn) {
+  const int band = GROUP_M * tiles_n;
+  const int g = t / band;
+  const int first = g * GROUP_M;
+  const int rows = min(tiles_m - first, GROUP_M);
+  const int r = t - g * band;
+  *tm = first + r % rows;
+  *tn = r / rows;
+}
+
+template <typename Cfg, int MODE, int DT>
+__global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NT = Cfg::NT;
+  constexpr int FM = Cfg::FM, FN = Cfg::FN, LDA = Cfg::LDA, LDB = Cfg::LDB;
+  constexpr int CA = Cfg::CA, CB = Cfg::CB;
+  extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+  unsigned short* const As = lds;                       // [2][BK][LDA]
+  unsigned short* const Bs = lds + 2 * Cfg::A_STAGE;    // [2][BK][LDB]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % Cfg::WAVES_M, wave_n = wave / Cfg::WAVES_M;
+
+  const int tiles = a.tiles_m * a.tiles_n;
+  const int total = (MODE == MODE_ACCUM) ? tiles : tiles * a.B;
+  const int item = xcd_remap(blockIdx.x, total);
+  const int sample0 = (MODE == MODE_ACCUM) ? 0 : item / tiles;
+  const int n_samples = (MODE == MODE_ACCUM) ? a.B : 1;
+  const int tile = (MODE == MODE_ACCUM) ? item : item - sample0 * tiles;
+  int tm, tn;
+  tile_coords<8>(tile, a.tiles_m, a.tiles_n, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // ---- global -> LDS copy plan: thread owns chunk column cc of rows r0, r0 + NT/(BM/8), ...
+  constexpr int A_CPR = BM / 8, B_CPR = BN / 8;           // chunks per row
+  constexpr int A_RSTEP = NT / A_CPR, B_RSTEP = NT / B_CPR;
+  const int a_row = tid / A_CPR, a_cc = tid % A_CPR;
+  const int b_row = tid / B_CPR, b_cc = tid % B_CPR;
+  const bool a_ok = m0 + a_cc * 8 < a.D;
+  const bool b_ok = n0 + b_cc * 8 < a.P;
+  // byte offsets inside one sample; an out-of-range column is sent to 2 GiB, beyond num_records, and reads 0
+  const uint32_t a_off0 = a_ok ? (uint32_t)(a_row * a.D + m0 + a_cc * 8) * 2u : 0x80000000u;
+  const uint32_t b_off0 = b_ok ? (uint32_t)(b_row * a.P + n0 + b_cc * 8) * 2u : 0x80000000u;
+  const uint32_t a_rstep = (uint32_t)(A_RSTEP * a.D) * 2u, b_rstep = (uint32_t)(B_RSTEP * a.P) * 2u;
+  const uint32_t a_kstep = (uint32_t)(BK * a.D) * 2u, b_kstep = (uint32_t)(BK * a.P) * 2u;
+  const uint32_t a_bytes = (uint32_t)a.T * (uint32_t)a.D * 2u, b_bytes = (uint32_t)a.T * (uint32_t)a.P * 2u;
+  const int a_lds_w = a_row * LDA + a_cc * 8, b_lds_w = b_row * LDB + b_cc * 8;   // element offsets in a stage
+
+  const int kt_per_sample = (a.T + BK - 1) / BK;
+  const int nk = kt_per_sample * n_samples;
+
+  u32x4_t ra[CA], rb[CB];
+  auto load_global = [&](int k) {
+    const int s = k / kt_per_sample, kt = k - s * kt_per_sample;
+    const char* pa = (const char*)a.dY + (size_t)(sample0 + s) * a_bytes;
+    const char* pb = (const char*)a.X + (size_t)(sample0 + s) * b_bytes;
+    const __amdgpu_buffer_rsrc_t rsa = make_rsrc(pa, a_bytes), rsb = make_rsrc(pb, b_bytes);
+    const uint32_t ao = a_off0 + (uint32_t)kt * a_kstep, bo = b_off0 + (uint32_t)kt * b_kstep;
+#pragma unroll
+    for (int j = 0; j < CA; ++j) ra[j] = __builtin_amdgcn_raw_buffer_load_b128(rsa, (int)(ao + j * a_rstep), 0, 0);
+#pragma unroll
+    for (int j = 0; j < CB; ++j) rb[j] = __builtin_amdgcn_raw_buffer_load_b128(rsb, (int)(bo + j * b_rstep), 0, 0);
+  };
+  auto store_lds = [&](int stage) {
+    unsigned short* pa = As + stage * Cfg::A_STAGE + a_lds_w;
+    unsigned short* pb = Bs + stage * Cfg::B_STAGE + b_lds_w;
+#pragma unroll
+    for (int j = 0; j < CA; ++j) *(u32x4_t*)(pa + j * A_RSTEP * LDA) = ra[j];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) *(u32x4_t*)(pb + j * B_RSTEP * LDB) = rb[j];
+  };
+
+  // ---- fragment read plan (see header): lane -> (row in the 16-row k-step, column in the 32-wide block)
+  const int f_row = 8 * (lane >> 5) + ((lane & 15) >> 2);
+  const int f_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const int a_lds_r = f_row * LDA + wave_m * Cfg::TM + f_col;
+  const int b_lds_r = f_row * LDB + wave_n * Cfg::TN + f_col;
+
+  f32x16_t acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  load_global(0);
+  store_lds(0);
+  if (nk > 1) load_global(1);
+  __syncthreads();
+
+  for (int k = 0; k < nk; ++k) {
+    const int cur = k & 1;
+    const unsigned short* pa = As + cur * Cfg::A_STAGE + a_lds_r;
+    const unsigned short* pb = Bs + cur * Cfg::B_STAGE + b_lds_r;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      s16x8_t fa[FM], fb[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const s16x4_t lo = lds_read_tr(pa + (ks * 16) * LDA + i * 32);
+        const s16x4_t hi = lds_read_tr(pa + (ks * 16 + 4) * LDA + i * 32);
+        fa[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const s16x4_t lo = lds_read_tr(pb + (ks * 16) * LDB + j * 32);
+        const s16x4_t hi = lds_read_tr(pb + (ks * 16 + 4) * LDB + j * 32);
+        fb[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma32<DT>(fa[i], fb[j], acc[i][j]);
+      if (ks == BK / 32) {   // halfway: hand the prefetched tile to the other stage, start the next fetch
+        if (k + 1 < nk) store_lds(cur ^ 1);
+        if (k + 2 < nk) load_global(k + 2);
+      }
+    }
+    if constexpr (MODE == MODE_ACCUM) {
+      // sample boundary: rescale so that acc always holds sum_{j<=i} (c_j / c_i) G_j; exact up to one
+      // fp32 rounding per boundary, and needs no second set of accumulators
+      if (a.factors != nullptr && (k + 1) % kt_per_sample == 0) {
+        const int s = k / kt_per_sample;
+        const float ratio = (s + 1 < n_samples) ? a.factors[s] / a.factors[s + 1] : a.factors[s];
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] *= ratio;
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue
+  const int row_base = m0 + wave_m * Cfg::TM + 4 * (lane >> 5);
+  const int col_base = n0 + wave_n * Cfg::TN + (lane & 31);
+  if constexpr (MODE == MODE_NORM || MODE == MODE_SPILL) {
+    // intra-block reduction of the squared norm: lane chain -> wave shuffle -> LDS across waves.
+    // Rows/columns beyond D/P were loaded as zeros and add nothing.
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) ss = fmaf(acc[i][j][e], acc[i][j][e], ss);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    float* red = (float*)lds;   // operand tiles are dead after the last barrier of the main loop
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    if (tid == 0) {
+      float tot = 0.0f;
+      for (int w = 0; w < NT / 64; ++w) tot += red[w];
+      a.partials[(size_t)sample0 * tiles + tile] = tot;
+    }
+    if constexpr (MODE == MODE_SPILL) {
+      unsigned short* sc = (unsigned short*)a.scratch + (size_t)sample0 * a.D * a.P;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int col = col_base + j * 32;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int row = row_base + i * 32 + 8 * (e >> 2) + (e & 3);
+            if (row < a.D && col < a.P) sc[(size_t)row * a.P + col] = to_16bit<DT>(acc[i][j][e]);
+          }
+        }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int col = col_base + j * 32;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = row_base + i * 32 + 8 * (e >> 2) + (e & 3);
+          if (row < a.D && col < a.P) a.out[(size_t)row * a.P + col] = acc[i][j][e];
+        }
+      }
+  }
+}
+
+}  // namespace flashdp

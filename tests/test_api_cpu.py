@@ -1,0 +1,91 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol the header
+declares, and rejects bad arguments before touching a device.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2507_01154_amd as F
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "flashdp.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(flashdp_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert "flashdp_linear_dp_grad" in names and "flashdp_block_dp_grad" in names and len(names) >= 14
+    L = F.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert F.flashdp_version() >= 100
+    assert F.status_string(0) == "ok" and "workspace" in F.status_string(F.WORKSPACE_TOO_SMALL)
+
+
+def test_binding_wraps_every_entry_point_by_name():
+    for n in declared_functions():
+        if n in ("flashdp_status_string",):
+            continue
+        assert hasattr(F, n), n
+
+
+A, B_, O_ = 0x10000, 0x20000, 0x30000      # fake, aligned, never dereferenced: every call below fails validation first
+
+
+@pytest.mark.parametrize("args,want", [
+    ((None, B_, 1, 1, 8, 8, 1.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, None, 1, 1, 8, 8, 1.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 8, 1.0, 0.0, 0, None, None), F.INVALID_ARGUMENT),
+    ((A, B_, 0, 1, 8, 8, 1.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, -3, 8, 8, 1.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 0, 8, 1.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 0, 1.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 8, 0.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 8, -1.0, 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 8, float("nan"), 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 8, float("inf"), 0.0, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 8, 1.0, -0.5, 0, O_, None), F.INVALID_ARGUMENT),
+    ((A, B_, 1, 1, 8, 8, 1.0, float("nan"), 0, O_, None), F.INVALID_ARGUMENT),
+    ((A + 8, B_, 1, 1, 8, 8, 1.0, 0.0, 0, O_, None), F.MISALIGNED),
+    ((A, B_ + 2, 1, 1, 8, 8, 1.0, 0.0, 0, O_, None), F.MISALIGNED),
+    ((A, B_, 1, 1, 8, 8, 1.0, 0.0, 0, O_ + 4, None), F.MISALIGNED),
+    ((A, B_, 1, 1 << 20, 1 << 12, 8, 1.0, 0.0, 0, O_, None), F.UNSUPPORTED_SHAPE),
+    ((A, B_, 1, 4, 8, 1 << 31, 1.0, 0.0, 0, O_, None), F.UNSUPPORTED_SHAPE),
+])
+def test_argument_validation(args, want):
+    assert F.lib().flashdp_linear_dp_grad(*args) == want
+
+
+def test_context_setters_validate():
+    L = F.lib()
+    assert L.flashdp_set_dtype(7) == F.INVALID_ARGUMENT and L.flashdp_set_dtype(F.BF16) == F.OK
+    assert L.flashdp_set_schedule(9) == F.INVALID_ARGUMENT and L.flashdp_set_schedule(0) == F.OK
+    assert L.flashdp_set_workspace(None, 16) == F.INVALID_ARGUMENT
+    assert L.flashdp_set_workspace(0x1008, 64) == F.MISALIGNED
+    assert L.flashdp_set_workspace(None, 0) == F.OK
+    assert L.flashdp_block_dp_grad(None, 1, 1, 1, 0, 0, None, 0, None) == F.INVALID_ARGUMENT
+    assert L.flashdp_plain_grad(A, B_, 1, 1, 8, 8, 5, O_, None) == F.INVALID_ARGUMENT
+    assert L.flashdp_noise_field(1, 0, 0, O_, None) == F.INVALID_ARGUMENT
+    assert L.flashdp_box_muller(None, 4, O_, None) == F.INVALID_ARGUMENT
+
+
+def test_workspace_bytes_formula():
+    mk = lambda p, d: dict(X=None, dY=None, d_in=p, d_out=d, C=1.0, sigma=1.0, seed=0, layer=0, out_grad=None)
+    B, T = 8, 2048
+    big = F.flashdp_workspace_bytes([mk(5120, 13824), mk(5120, 5120)], B, T, F.BF16, "scratch")
+    assert big >= B * 5120 * 13824 * 2 and big < B * 5120 * 13824 * 2 + (1 << 20)      # 16-bit scratch of the largest layer
+    assert F.flashdp_workspace_bytes([mk(5120, 13824)], B, T, F.F32, "scratch") >= B * 5120 * 13824 * 4
+    assert 0 < F.flashdp_workspace_bytes([mk(5120, 13824)], B, T, F.BF16, "twopass") < (1 << 20)
+    assert F.flashdp_workspace_bytes([mk(0, 8)], B, T, F.BF16, "scratch") == 0
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a host without a GPU")
+def test_no_device_is_an_error_not_a_crash():
+    assert F.lib().flashdp_linear_dp_grad(A, B_, 1, 1, 8, 8, 1.0, 0.0, 0, O_, None) == F.NO_DEVICE
+    assert F.lib().flashdp_noise_field(1, 0, 16, O_, None) == F.NO_DEVICE

@@ -1,0 +1,261 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the same
+seeded stored inputs.
+
+Tolerances (relative Frobenius error of out_grad against the oracle):
+  * stated for this path: 1e-2 for 16-bit inputs, 1e-4 for fp32 inputs; per-sample norms 5e-3 relative;
+  * derived from the arithmetic and asserted as well, so that a partial bug cannot hide in the slack:
+      - two-pass schedule and fp32 inputs: fp32 accumulation only (products of 16-bit inputs are exact in
+        fp32), error ~ sqrt(T) * 2^-24, asserted <= 5e-5;
+      - scratch schedule, 16-bit inputs: one extra rounding of G_i to 16 bits, rms 2^-9 / sqrt(3) ~ 1.1e-3
+        relative for bf16, asserted <= 4e-3;
+      - norms come from the fp32 accumulators before any 16-bit rounding: asserted <= 1e-4;
+      - noise field: |z_gpu - z_oracle| <= 2e-6 per element (fp32 Box-Muller on exact 24-bit uniforms; the
+        host build of the same header measures 6e-7), so out(sigma) - out(0) is compared at 4e-6 * sigma * C
+        max-abs (one more fp32 rounding of the sum) and 1e-6 relative Frobenius.
+The noisy output alone is never the only check: with sigma = 1 the noise dwarfs the clipped signal.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flashdp_oracle as O
+import workloads as W
+import paper_2507_01154_amd as F
+from gpu_util import DEV, rel_fro, run_layer, to_device, env
+
+pytestmark = pytest.mark.gpu
+
+TOL_STATED = {"bf16": 1e-2, "f16": 1e-2, "fp32": 1e-4}
+TOL_NORM_STATED = 5e-3
+
+
+def tight_tol(dtype, schedule):
+    if dtype == "fp32" or schedule == "twopass":
+        return 5e-5
+    return 4e-3 if dtype == "bf16" else 6e-4   # f16 keeps 11 significant bits
+
+
+def check_case(X, dY, C, sigma, seed, layer, dtype, schedule, tile=None, oracle=None):
+    """The four-part protocol; returns realised errors for logging."""
+    D, P = dY.shape[2], X.shape[2]
+    want0, wn = oracle if oracle is not None else O.linear_dp_grad(X, dY, C, 0.0, seed, layer)
+    got0, gn, used = run_layer(X, dY, C, 0.0, seed, layer, schedule, tile=tile)
+    if schedule != "auto":
+        assert used == schedule
+    assert np.all(np.isfinite(got0)) and np.all(np.isfinite(gn))
+    e_sig = rel_fro(got0, want0)
+    e_norm = float(np.max(np.abs(gn - wn) / np.maximum(wn, 1e-300))) if np.all(wn > 0) else float(np.max(np.abs(gn - wn)))
+    assert e_sig <= TOL_STATED[dtype], (e_sig, used)
+    assert e_sig <= tight_tol(dtype, used), (e_sig, used)
+    assert e_norm <= TOL_NORM_STATED and e_norm <= 1e-4, e_norm
+    e_noise = 0.0
+    if sigma > 0:
+        got1, gn1, _ = run_layer(X, dY, C, sigma, seed, layer, schedule, tile=tile)
+        z = O.noise_field(seed, layer, D * P).reshape(D, P)
+        diff = got1.astype(np.float64) - got0.astype(np.float64)
+        e_noise = float(np.max(np.abs(diff - sigma * C * z)))
+        assert e_noise <= 4e-6 * sigma * C * max(1.0, float(np.max(np.abs(got0))) / (sigma * C)), e_noise
+        assert rel_fro(diff, sigma * C * z) <= 1e-6
+        assert rel_fro(got1, want0 + sigma * C * z) <= TOL_STATED[dtype]
+        assert np.array_equal(gn1, gn)                      # noise never touches the norms
+    return e_sig, e_norm, e_noise, used
+
+
+# ---------------------------------------------------------------------------------------------------
+# noise generator on its own
+# ---------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed,layer,n", [(1, 0, 1 << 20), ((5 << 32) | 77, 6, 1000003), (0, 0xFFFFFFFF, 7), (3, 2, 4096)])
+def test_noise_field_matches_oracle(seed, layer, n):
+    z = torch.full((n + 8,), float("nan"), device=DEV)
+    F.flashdp_noise_field(seed, layer, n, z)
+    torch.cuda.synchronize()
+    got = z.cpu().numpy()
+    assert np.all(np.isnan(got[n:]))                        # nothing written past n
+    want = O.noise_field(seed, layer, n)
+    assert np.max(np.abs(got[:n] - want)) <= 2e-6
+
+
+def test_box_muller_edge_words():
+    edge = [0, 255, 256, 0xFFFFFFFF, 0xFFFFFF00, 0x80000000, 0x7FFFFFFF, 0x40000000, 0x3FFFFFFF, 0xC0000000,
+            0xBFFFFFFF, 0x20000000, 0xE0000000, 0x100, 0x200, 0x5FFFFFFF, 0x60000000, 0x2FFFFFFF, 0x30000000]
+    w = np.array([(a, b, b, a) for a in edge for b in edge], dtype=np.uint32)
+    rng = np.random.default_rng(3)
+    w = np.concatenate([w, rng.integers(0, 1 << 32, size=(1 << 18, 4), dtype=np.uint64).astype(np.uint32)])
+    dw = torch.from_numpy(w.view(np.int32)).to(DEV)
+    z = torch.empty(w.shape, device=DEV, dtype=torch.float32)
+    F.flashdp_box_muller(dw, w.shape[0], z)
+    torch.cuda.synchronize()
+    want = O.gaussians_from_words(w)
+    assert np.max(np.abs(z.cpu().numpy() - want)) <= 2e-6
+
+
+# ---------------------------------------------------------------------------------------------------
+# configuration 1 (tiny, fp32) and its companion
+# ---------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("schedule", ["twopass", "scratch"])
+@pytest.mark.parametrize("C", [1.0, 20.0])
+def test_tiny_fp32(schedule, C):
+    w = W.WORKLOADS["tiny_fp32"]
+    X, dY = W.make_layer(w, 0)
+    e = check_case(X, dY, C, 1.0, w.noise_seed, 0, "fp32", schedule)
+    print("tiny_fp32", schedule, C, e)
+
+
+# ---------------------------------------------------------------------------------------------------
+# small shapes spanning several tiles with ragged edges, every kernel variant
+# ---------------------------------------------------------------------------------------------------
+
+SMALL = [
+    # B, T, d_in, d_out
+    (3, 200, 328, 520),      # several 128/256 tiles, ragged in every dimension, T not a multiple of 64
+    (2, 64, 256, 256),       # exactly one 256 tile, one k-tile
+    (5, 1, 8, 8),            # T = 1, smallest matrix-core shape
+    (2, 130, 264, 24),       # thin output
+]
+
+
+@pytest.mark.parametrize("shape", SMALL)
+@pytest.mark.parametrize("schedule", ["twopass", "scratch"])
+@pytest.mark.parametrize("tile", [1, 2, 3])
+def test_small_bf16_all_tiles(shape, schedule, tile):
+    B, T, P, D = shape
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    e = check_case(X, dY, 1.0, 1.0, 11, 3, "bf16", schedule, tile=tile)
+    print(shape, schedule, tile, e)
+
+
+@pytest.mark.parametrize("schedule", ["twopass", "scratch"])
+def test_odd_dims_take_generic_kernel(schedule):
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=3, T=37, dims=[(77, 131)])
+    X, dY = W.make_layer(w, 0)
+    check_case(X, dY, 1.0, 0.5, 5, 1, "bf16", schedule)
+
+
+@pytest.mark.parametrize("schedule", ["twopass", "scratch"])
+@pytest.mark.parametrize("shape", [(3, 100, 136, 264), (2, 33, 50, 70)])
+def test_f16_and_fp32_inputs(schedule, shape):
+    B, T, P, D = shape
+    rng = np.random.default_rng(B * T)
+    X32 = rng.standard_normal((B, T, P)).astype(np.float32)
+    dY32 = (rng.standard_normal((B, T, D)) * 0.05 * (10.0 ** rng.uniform(-1, 1, size=(B, 1, 1)))).astype(np.float32)
+    check_case(X32, dY32, 1.0, 1.0, 9, 2, "fp32", schedule)
+    X16, dY16 = X32.astype(np.float16), dY32.astype(np.float16)
+    want = O.linear_dp_grad(X16.astype(np.float32), dY16.astype(np.float32), 1.0, 0.0, 9, 2)
+    check_case(X16, dY16, 1.0, 1.0, 9, 2, "f16", schedule, oracle=want)
+
+
+def test_clip_branches_and_degenerate_inputs():
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=4, T=96, dims=[(128, 136)])
+    X, dY = W.make_layer(w, 0)
+    _, norms = O.linear_dp_grad(X, dY, 1.0, 0.0, 0)
+    C = float(np.sort(norms)[1] * 1.5)          # two samples below the threshold, two above
+    assert np.sum(norms < C) == 2
+    for schedule in ("twopass", "scratch"):
+        check_case(X, dY, C, 0.0, 0, 0, "bf16", schedule)
+    # a sample with zero gradient: norm 0, factor 1, no NaN
+    dY0 = dY.copy()
+    dY0[1] = 0
+    for schedule in ("twopass", "scratch"):
+        got, gn, _ = run_layer(X, dY0, 1.0, 0.0, 0, 0, schedule)
+        want, wn = O.linear_dp_grad(X, dY0, 1.0, 0.0, 0)
+        assert gn[1] == 0.0 and np.all(np.isfinite(got)) and rel_fro(got, want) <= 4e-3
+    # B = 1
+    check_case(X[:1], dY[:1], 1.0, 1.0, 4, 0, "bf16", "scratch")
+    check_case(X[:1], dY[:1], 1.0, 1.0, 4, 0, "bf16", "twopass")
+
+
+def test_plain_grad_is_the_unclipped_limit():
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=3, T=160, dims=[(264, 392)])
+    X, dY = W.make_layer(w, 0)
+    B, T, P = X.shape
+    D = dY.shape[2]
+    dX, ddY = to_device(X), to_device(dY)
+    want = O.widen(dY).reshape(B * T, D).T @ O.widen(X).reshape(B * T, P)        # Eq. batched-grad
+    for tile in (1, 2, 3):
+        out = torch.full((D, P), float("nan"), device=DEV)
+        with env(FLASHDP_TILE=tile):
+            F.flashdp_plain_grad(dX, ddY, B, T, P, D, F.BF16, out)
+        torch.cuda.synchronize()
+        assert rel_fro(out.cpu().numpy(), want) <= 5e-6
+    got, _, _ = run_layer(X, dY, 1e30, 0.0, 0, 0, "twopass")
+    assert rel_fro(got, want) <= 5e-6
+
+
+def test_repeatable_and_workspace_argument():
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=4, T=128, dims=[(384, 520)])
+    X, dY = W.make_layer(w, 0)
+    a = run_layer(X, dY, 1.0, 1.0, 7, 1, "scratch")
+    b = run_layer(X, dY, 1.0, 1.0, 7, 1, "scratch")
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])             # fixed-order reductions: bit-repeatable
+    B, T, P = X.shape
+    D = dY.shape[2]
+    L = [dict(X=None, dY=None, d_in=P, d_out=D, C=1.0, sigma=1.0, seed=7, layer=1, out_grad=None)]
+    need = F.flashdp_workspace_bytes(L, B, T, F.BF16, "scratch")
+    small = F.flashdp_workspace_bytes(L, B, T, F.BF16, "twopass")
+    assert need >= B * D * P * 2 and 0 < small < 65536
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    c = run_layer(X, dY, 1.0, 1.0, 7, 1, "scratch", workspace=ws)
+    assert np.array_equal(a[0], c[0])
+    d = run_layer(X, dY, 1.0, 1.0, 7, 1, "auto", workspace=ws[:small])           # too small for scratch: auto falls back
+    assert d[2] == "twopass"
+    with pytest.raises(F.FlashDPError) as ei:
+        run_layer(X, dY, 1.0, 1.0, 7, 1, "scratch", workspace=ws[: need - 256])
+    assert ei.value.status == F.WORKSPACE_TOO_SMALL
+
+
+def test_eleven_argument_entry_point_uses_context():
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=2, T=64, dims=[(136, 264)])
+    X, dY = W.make_layer(w, 0)
+    B, T, P = X.shape
+    D = dY.shape[2]
+    dX, ddY = to_device(X), to_device(dY)
+    out = torch.empty((D, P), device=DEV)
+    norms = torch.empty((B,), device=DEV)
+    F.flashdp_set_stream(None)
+    F.flashdp_set_dtype(F.BF16)
+    F.flashdp_set_layer(5)
+    F.flashdp_set_schedule("auto")
+    F.flashdp_set_workspace(None)
+    F.flashdp_linear_dp_grad(dX, ddY, B, T, P, D, 1.0, 0.7, 123, out, norms)
+    torch.cuda.synchronize()
+    want, wn = O.linear_dp_grad(X, dY, 1.0, 0.7, 123, layer=5)
+    assert rel_fro(out.cpu().numpy(), want) <= 1e-2
+    z = O.noise_field(123, 5, D * P).reshape(D, P)
+    sig, _ = O.linear_dp_grad(X, dY, 1.0, 0.0, 123, 5)
+    assert rel_fro(out.cpu().numpy() - 0.7 * z, sig) <= 4e-3                     # the signal under the noise
+    assert np.max(np.abs(norms.cpu().numpy() - wn) / wn) <= 1e-4
+    F.flashdp_set_layer(0)
+
+
+def test_block_variant_matches_layerwise_oracle():
+    base = W.WORKLOADS["llama13b_block"]
+    dims = [(128, 128), (128, 128), (128, 128), (128, 128), (128, 344), (128, 344), (344, 128)]
+    w = W.scaled_down(base, B=3, T=96, dims=dims)
+    layers, keep = [], []
+    for l in range(len(dims)):
+        X, dY = W.make_layer(w, l)
+        P, D = dims[l]
+        out = torch.full((D, P), float("nan"), device=DEV)
+        norms = torch.full((w.B,), float("nan"), device=DEV)
+        layers.append(dict(X=to_device(X), dY=to_device(dY), d_in=P, d_out=D, C=w.C, sigma=w.sigma,
+                           seed=w.layer_seed(l), layer=l, out_grad=out, out_norms=norms))
+        keep.append((X, dY))
+    for schedule in ("scratch", "twopass"):
+        F.flashdp_block_dp_grad(layers, w.B, w.T, F.BF16, schedule)
+        torch.cuda.synchronize()
+        for l, (X, dY) in enumerate(keep):
+            sig, wn = O.linear_dp_grad(X, dY, w.C, 0.0, w.layer_seed(l), l)
+            P, D = dims[l]
+            z = O.noise_field(w.layer_seed(l), l, D * P).reshape(D, P)
+            got = layers[l]["out_grad"].cpu().numpy()
+            assert rel_fro(got - w.sigma * w.C * z, sig) <= tight_tol("bf16", schedule) + 1e-4   # fp32 cancellation of the noise
+            assert np.max(np.abs(layers[l]["out_norms"].cpu().numpy() - wn) / wn) <= 1e-4
