@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-layer DP weight-gradient path (Algorithm 1 of FlashDP) on one MI355X.
+
+A step is one pass of the whole path - per-sample contraction, norm reduction, clip factors, clipped
+batch sum, Philox noise, store - over every linear layer of the workload (default: the seven linears of
+a Llama-13B decoder block, B = 8, T = 2048, bf16), inputs resident in HBM.  Prints one JSON line:
+throughput in algorithmic TFLOP/s (2*B*T*d_in*d_out per layer, one contraction per layer whatever the
+schedule does), its fraction of the dense bf16 MFMA peak, the ratio against the plain non-DP dY^T X
+weight-gradient GEMM timed in the same run (the faster of the vendor BLAS through torch.matmul and this
+library's own contraction with norm/clip/noise switched off), a roofline object for the dominant kernel
+(timed alone, live, with events on the launch stream) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama13b_block")
+    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-comparators", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device copy: a kernel of known traffic to scale profiler byte counters by")
+    return ap.parse_args()
+
+
+def time_steps(fn, steps, warmup):
+    """Wall-clock over exactly `steps` calls, bracketed by device synchronisation; ms per step."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def time_events(fn, steps, warmup):
+    """Device time per call from events recorded on the current stream (the stream the library launches on)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    s = torch.cuda.Event(enable_timing=True)
+    e = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s.record()
+    for _ in range(steps):
+        fn()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) / steps
+
+
+def cpu_baseline(w):
+    """The oracle as it stands on the host cores, on a bounded sample of the same workload: the largest
+    layer of the workload, full T, as many samples as keep the work near 10-30 s."""
+    import numpy as np
+    import workloads as W
+    from oracle import flashdp_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    l = max(range(len(w.layers)), key=lambda k: w.layers[k].d_in * w.layers[k].d_out)
+    spec = w.layers[l]
+    per_sample = 2.0 * w.T * spec.d_in * spec.d_out
+    n = int(max(1, min(w.B, round(2.4e12 / per_sample))))
+    Xs, dYs = zip(*[W.make_sample(w, l, i) for i in range(n)])
+    X, dY = np.stack(Xs), np.stack(dYs)
+    t0 = time.perf_counter()
+    O.linear_dp_grad(X, dY, w.C, w.sigma, w.layer_seed(l), l)
+    dt = time.perf_counter() - t0
+    return {"value": round(n * per_sample / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": f"layer {spec.name} ({spec.d_in}->{spec.d_out}), {n} of {w.B} samples, T={w.T}, fp64 numpy oracle incl. noise field"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads as W
+    import paper_2507_01154_amd as F
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    F.lib()   # fail loudly if the HIP library is missing
+    w = W.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    dtype_code = F.BF16 if w.dtype == "bf16" else F.F32
+    layers, keep = [], []
+    for l, spec in enumerate(w.layers):
+        X, dY = W.make_layer_device(w, l, dev)
+        out = torch.empty((spec.d_out, spec.d_in), dtype=torch.float32, device=dev)
+        norms = torch.empty((w.B,), dtype=torch.float32, device=dev)
+        layers.append(dict(X=X, dY=dY, d_in=spec.d_in, d_out=spec.d_out, C=w.C, sigma=w.sigma,
+                           seed=w.layer_seed(l), layer=l, out_grad=out, out_norms=norms))
+        keep.append((X, dY, out, norms))
+    arr = F.make_layers(layers)
+    sched = args.schedule
+    ws = None
+    if sched != "twopass":
+        ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, "scratch"), dtype=torch.uint8, device=dev)
+
+    def step():
+        F.flashdp_block_dp_grad(arr, w.B, w.T, dtype_code, sched, ws)
+
+    ms = time_steps(step, args.steps, args.warmup)
+    used = F.flashdp_last_schedule()
+    flops = float(w.flops())
+    tflops = flops / ms / 1e9
+
+    # dominant kernel alone (the per-sample contraction + intra-block norm), same launches, same stream
+    F.flashdp_set_stages(F.STAGE_CONTRACT)
+    ms_contract = time_events(step, args.steps, 2)
+    F.flashdp_set_stages(F.STAGE_AGGREGATE)
+    ms_aggregate = time_events(step, args.steps, 2)
+    F.flashdp_set_stages(F.STAGE_ALL)
+    step()
+    torch.cuda.synchronize()
+    hw_flops = flops * (2.0 if used == "twopass" else 1.0)
+    n_launch = len(w.layers)
+    roofline = {
+        "bound": "mfma", "kernel": "gemm_mfma_kernel (per-sample contraction + norm)",
+        "achieved": round(flops / ms_contract / 1e9, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(flops / ms_contract / 1e9 / PEAK_BF16_TFLOPS, 4),
+        "launches_per_step": n_launch, "avg_launch_ms": round(ms_contract / n_launch, 4),
+        "flops_per_launch": flops / n_launch, "traffic": None,
+    }
+
+    result = {
+        "metric": "dp_weight_grad_tflops", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "T": w.T,
+                   "layers": [f"{s.name}:{s.d_in}->{s.d_out}" for s in w.layers],
+                   "C": w.C, "sigma": w.sigma, "schedule": used},
+        "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "hardware_flops_per_step": hw_flops,
+        "stage_ms": {"contract": round(ms_contract, 4), "aggregate_and_noise": round(ms_aggregate, 4)},
+        "roofline": roofline,
+    }
+
+    if not args.no_comparators:
+        # non-DP comparators: dY^T X over K = B*T (Eq. batched-grad), same inputs
+        def blas():
+            for (X, dY, out, _) in keep:
+                torch.matmul(dY.view(-1, dY.shape[-1]).t(), X.view(-1, X.shape[-1]))
+
+        def own():
+            for (X, dY, out, _), spec in zip(keep, w.layers):
+                F.flashdp_plain_grad(X, dY, w.B, w.T, spec.d_in, spec.d_out, dtype_code, out)
+
+        ms_blas = time_steps(blas, args.steps, 3)
+        ms_own = time_steps(own, args.steps, 3)
+        best = min(ms_blas, ms_own)
+        result["nondp"] = {"torch_matmul_ms": round(ms_blas, 4), "torch_matmul_tflops": round(flops / ms_blas / 1e9, 2),
+                           "own_plain_ms": round(ms_own, 4), "own_plain_tflops": round(flops / ms_own / 1e9, 2)}
+        result["ratio_vs_nondp"] = round(best / ms, 4)
+        # restore the outputs of a full DP step
+        step()
+        torch.cuda.synchronize()
+
+    if args.copy_probe:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        result["copy_probe_bytes_each_way"] = 1 << 30
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -128,6 +128,13 @@ int flashdp_set_dtype(int dtype);
 int flashdp_set_layer(uint32_t layer);
 int flashdp_set_schedule(int schedule);
 
+/* Measurement aid: which stages of Algorithm 1 the following calls on this thread enqueue (default: all).
+ * With a partial mask the outputs are not meaningful; the stages left out read whatever the workspace
+ * holds from an earlier full call.  CONTRACT = per-sample contraction + intra-block norm (the dominant
+ * kernel), CLIP = inter-block reduce and clip factors, AGGREGATE = clipped batch sum + noise. */
+enum { FLASHDP_STAGE_CONTRACT = 1, FLASHDP_STAGE_CLIP = 2, FLASHDP_STAGE_AGGREGATE = 4, FLASHDP_STAGE_ALL = 7 };
+int flashdp_set_stages(int mask);
+
 /* Frees the library-owned workspaces (synchronises the device first). */
 int flashdp_release(void);
 

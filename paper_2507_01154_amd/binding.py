@@ -69,8 +69,9 @@ def lib() -> ctypes.CDLL:
         L.flashdp_set_dtype.argtypes = [ci]
         L.flashdp_set_layer.argtypes = [u32]
         L.flashdp_set_schedule.argtypes = [ci]
+        L.flashdp_set_stages.argtypes = [ci]
         for n in ("flashdp_set_stream", "flashdp_set_workspace", "flashdp_set_dtype", "flashdp_set_layer",
-                  "flashdp_set_schedule", "flashdp_release", "flashdp_version"):
+                  "flashdp_set_schedule", "flashdp_set_stages", "flashdp_release", "flashdp_version"):
             getattr(L, n).restype = ci
         L.flashdp_last_schedule.restype = ctypes.c_char_p
         L.flashdp_status_string.argtypes = [ci]
@@ -134,6 +135,13 @@ def flashdp_set_layer(layer: int):
 
 def flashdp_set_schedule(schedule):
     _check(lib().flashdp_set_schedule(schedule_code(schedule)), "flashdp_set_schedule")
+
+
+STAGE_CONTRACT, STAGE_CLIP, STAGE_AGGREGATE, STAGE_ALL = 1, 2, 4, 7
+
+
+def flashdp_set_stages(mask: int = STAGE_ALL):
+    _check(lib().flashdp_set_stages(int(mask)), "flashdp_set_stages")
 
 
 def flashdp_release():

@@ -26,6 +26,7 @@ struct Context {
   int dtype = FLASHDP_BF16;
   uint32_t layer = 0;
   int schedule = FLASHDP_SCHEDULE_AUTO;
+  int stages = FLASHDP_STAGE_ALL;
   const char* last_schedule = "none";
 };
 thread_local Context g_ctx;
@@ -221,6 +222,7 @@ size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype,
 
 // Enqueues Algorithm 1 for one layer.
 int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool use_scratch, char* ws, hipStream_t st) {
+  const int stages = g_ctx.stages;
   const int64_t P = L.d_in, D = L.d_out;
   const Plan plan = make_plan(B, T, P, D, dtype);
   const WsLayout wl = ws_layout(plan, B, P, D, dtype, use_scratch);
@@ -238,16 +240,21 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool us
   const float noise_scale = L.sigma * L.C;
 
   if (use_scratch) {
-    HIP_TRY(launch_gemm<MODE_SPILL>(plan, dtype, a, st));
-    hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, st));
+    if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_SPILL>(plan, dtype, a, st));
+    if (stages & FLASHDP_STAGE_CLIP) {
+      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
+      HIP_TRY(hipGetLastError());
+    }
+    if (stages & FLASHDP_STAGE_AGGREGATE)
+      HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, st));
   } else {
-    HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
-    hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, st));
-    if (noise_scale != 0.0f) {
+    if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
+    if (stages & FLASHDP_STAGE_CLIP) {
+      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
+      HIP_TRY(hipGetLastError());
+    }
+    if (stages & FLASHDP_STAGE_AGGREGATE) HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, st));
+    if ((stages & FLASHDP_STAGE_AGGREGATE) && noise_scale != 0.0f) {
       const size_t groups = (S + 3) / 4;
       hipLaunchKernelGGL((noise_kernel<true>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, L.out_grad, S, noise_scale, L.seed, L.layer);
       HIP_TRY(hipGetLastError());
@@ -384,6 +391,12 @@ int flashdp_set_layer(uint32_t layer) { g_ctx.layer = layer; return FLASHDP_OK; 
 int flashdp_set_schedule(int schedule) {
   if (!valid_schedule(schedule)) return FLASHDP_INVALID_ARGUMENT;
   g_ctx.schedule = schedule;
+  return FLASHDP_OK;
+}
+
+int flashdp_set_stages(int mask) {
+  if (mask <= 0 || mask > FLASHDP_STAGE_ALL) return FLASHDP_INVALID_ARGUMENT;
+  g_ctx.stages = mask;
   return FLASHDP_OK;
 }
 

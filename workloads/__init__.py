@@ -168,3 +168,22 @@ def scaled_down(w: Workload, B: int | None = None, T: int | None = None,
         layers = tuple(LayerSpec(f"l{k}", di, do) for k, (di, do) in enumerate(dims))
     return Workload(name or (w.name + "_small"), w.dtype, B or w.B, T or w.T, layers,
                     w.dy_variance, w.scale_rule, w.C, w.sigma, w.data_seed, w.noise_seed)
+
+
+def make_layer_device(w: Workload, layer: int, device: str = "cuda:0"):
+    """Same recipe as make_layer, drawn on the device with torch's seeded generator (another stream of
+    numbers, same distributions): for the benchmark, where 3 GB of host draws would dominate the run.
+    Returns torch tensors (X [B,T,P], dY [B,T,D]) of the workload's dtype."""
+    import torch
+
+    spec = w.layers[layer]
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=device)
+    g.manual_seed((w.data_seed << 8) + layer)
+    scales = torch.tensor(np.sqrt(w.dy_variance) * sample_scales(w, layer), dtype=torch.float32, device=device)
+    X = torch.empty((w.B, w.T, spec.d_in), dtype=dt, device=device)
+    dY = torch.empty((w.B, w.T, spec.d_out), dtype=dt, device=device)
+    for i in range(w.B):       # sample by sample: the fp32 draw is transient
+        X[i] = torch.randn((w.T, spec.d_in), generator=g, device=device, dtype=torch.float32).to(dt)
+        dY[i] = (torch.randn((w.T, spec.d_out), generator=g, device=device, dtype=torch.float32) * scales[i]).to(dt)
+    return X, dY
