@@ -14,8 +14,12 @@
 // i receives element (i % 4) of lanes (i / 4), (i / 4) + 4, (i / 4) + 8, (i / 4) + 12.  So lane s points
 // at row (s / 4), column 4 * (s % 4) of a 4 (t) x 16 (m) block and lane i gets column i for 4 rows.
 //
-// v_mfma_f32_32x32x16 (bf16 or f16): lane l holds A[m = l % 32][k = 8 * (l / 32) + 0..7], likewise B with
-// n = l % 32; accumulator register j of lane l is C[row = 8 * (j / 4) + 4 * (l / 32) + (j % 4)][col = l % 32].
+// v_mfma_f32_32x32x16 (bf16 or f16): lane l holds A[r = l % 32][k = 8 * (l / 32) + 0..7], likewise B with
+// c = l % 32; accumulator register j of lane l is C[row = 8 * (j / 4) + 4 * (l / 32) + (j % 4)][col = l % 32].
+// The X fragment is passed as the first (row) operand and the dY fragment as the second, i.e. the
+// instruction forms the transposed block: lane l then owns output row m = l % 32 and, in registers
+// 4q..4q+3, four CONSECUTIVE output columns n = 8q + 4 * (l / 32) + 0..3, which the epilogue packs into one
+// 8-byte (16-bit scratch) or 16-byte (fp32) store instead of four scattered ones.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -82,6 +86,20 @@ __device__ __forceinline__ unsigned short to_16bit(float v) {
     return __builtin_bit_cast(unsigned short, (__bf16)v);
   } else {
     return __builtin_bit_cast(unsigned short, (_Float16)v);
+  }
+}
+
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+
+template <int DT>
+__device__ __forceinline__ uint32_t pack2_16bit(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  if constexpr (DT == DT_BF16) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+  } else {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
   }
 }
 
@@ -181,38 +199,56 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+  // Fragments are double-buffered: the transposed LDS reads of k-step ks+1 are issued before the
+  // matrix-core work of k-step ks, and the first reads of the next k-tile right after the barrier,
+  // ahead of the last k-step of this tile.
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of k-steps per tile");
+  s16x8_t fa[2][FM], fb[2][FN];
+  auto load_frags = [&](int stage, int ks, s16x8_t* pfa, s16x8_t* pfb) {
+    const unsigned short* pa = As + stage * Cfg::A_STAGE + a_lds_r + ks * 16 * LDA;
+    const unsigned short* pb = Bs + stage * Cfg::B_STAGE + b_lds_r + ks * 16 * LDB;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const s16x4_t lo = lds_read_tr(pa + i * 32);
+      const s16x4_t hi = lds_read_tr(pa + 4 * LDA + i * 32);
+      pfa[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const s16x4_t lo = lds_read_tr(pb + j * 32);
+      const s16x4_t hi = lds_read_tr(pb + 4 * LDB + j * 32);
+      pfb[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
+
   load_global(0);
   store_lds(0);
   if (nk > 1) load_global(1);
   __syncthreads();
+  load_frags(0, 0, fa[0], fb[0]);
 
   for (int k = 0; k < nk; ++k) {
     const int cur = k & 1;
-    const unsigned short* pa = As + cur * Cfg::A_STAGE + a_lds_r;
-    const unsigned short* pb = Bs + cur * Cfg::B_STAGE + b_lds_r;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      s16x8_t fa[FM], fb[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const s16x4_t lo = lds_read_tr(pa + (ks * 16) * LDA + i * 32);
-        const s16x4_t hi = lds_read_tr(pa + (ks * 16 + 4) * LDA + i * 32);
-        fa[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cb = ks & 1, nb = cb ^ 1;
+      if (ks + 1 < KS) {
+        load_frags(cur, ks + 1, fa[nb], fb[nb]);
+      } else {
+        __syncthreads();   // tile k+1 is in LDS, and every wave has read the last fragments of tile k
+        if (k + 1 < nk) load_frags(cur ^ 1, 0, fa[nb], fb[nb]);
       }
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const s16x4_t lo = lds_read_tr(pb + (ks * 16) * LDB + j * 32);
-        const s16x4_t hi = lds_read_tr(pb + (ks * 16 + 4) * LDB + j * 32);
-        fb[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      if (ks == (KS >= 4 ? KS / 2 - 1 : 0)) {
+        if (k + 1 < nk) store_lds(cur ^ 1);      // hand the prefetched tile to the other stage
+      }
+      if (ks == KS - 2) {
+        if (k + 2 < nk) load_global(k + 2);      // and start the next fetch into the freed registers
       }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma32<DT>(fa[i], fb[j], acc[i][j]);
-      if (ks == BK / 32) {   // halfway: hand the prefetched tile to the other stage, start the next fetch
-        if (k + 1 < nk) store_lds(cur ^ 1);
-        if (k + 2 < nk) load_global(k + 2);
-      }
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma32<DT>(fb[cb][j], fa[cb][i], acc[i][j]);
     }
     if constexpr (MODE == MODE_ACCUM) {
       // sample boundary: rescale so that acc always holds sum_{j<=i} (c_j / c_i) G_j; exact up to one
@@ -228,12 +264,12 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
             for (int e = 0; e < 16; ++e) acc[i][j][e] *= ratio;
       }
     }
-    __syncthreads();
   }
+  __syncthreads();   // the reduction below reuses the LDS tiles
 
-  // ---- epilogue
-  const int row_base = m0 + wave_m * Cfg::TM + 4 * (lane >> 5);
-  const int col_base = n0 + wave_n * Cfg::TN + (lane & 31);
+  // ---- epilogue.  acc[i][j][4q + r] = G[m0 + wave_m*TM + 32i + lane%32][n0 + wave_n*TN + 32j + 8q + 4(lane/32) + r]
+  const int row_base = m0 + wave_m * Cfg::TM + (lane & 31);
+  const int col_base = n0 + wave_n * Cfg::TN + 4 * (lane >> 5);
   if constexpr (MODE == MODE_NORM || MODE == MODE_SPILL) {
     // intra-block reduction of the squared norm: lane chain -> wave shuffle -> LDS across waves.
     // Rows/columns beyond D/P were loaded as zeros and add nothing.
@@ -246,8 +282,27 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
         for (int e = 0; e < 16; ++e) ss = fmaf(acc[i][j][e], acc[i][j][e], ss);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-    float* red = (float*)lds;   // operand tiles are dead after the last barrier of the main loop
+    // The operand tiles are dead after the barrier that follows the main loop; LDS now stages the
+    // 16-bit tile (row pitch BN + 8 elements) so that it leaves the chip in full rows, and holds the
+    // per-wave partial sums behind it.
+    constexpr int EP = BN + 8;                               // pitch in elements: 16-byte aligned rows
+    static_assert(BM * EP * 2 + 64 <= Cfg::LDS_BYTES, "epilogue staging must fit in the operand buffers");
+    float* red = (float*)(lds + BM * EP);
     if (lane == 0) red[wave] = ss;
+    if constexpr (MODE == MODE_SPILL) {
+      unsigned short* st = lds + (wave_m * Cfg::TM + (lane & 31)) * EP + wave_n * Cfg::TN + 4 * (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            uint2 v;
+            v.x = pack2_16bit<DT>(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+            v.y = pack2_16bit<DT>(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            *(uint2*)(st + (i * 32) * EP + j * 32 + 8 * q) = v;
+          }
+    }
     __syncthreads();
     if (tid == 0) {
       float tot = 0.0f;
@@ -255,31 +310,33 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
       a.partials[(size_t)sample0 * tiles + tile] = tot;
     }
     if constexpr (MODE == MODE_SPILL) {
+      // 16 bytes per lane, BN/8 lanes per row: every store instruction writes whole 2*BN-byte rows
       unsigned short* sc = (unsigned short*)a.scratch + (size_t)sample0 * a.D * a.P;
+      constexpr int CPR = BN / 8;
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int col = col_base + j * 32;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int row = row_base + i * 32 + 8 * (e >> 2) + (e & 3);
-            if (row < a.D && col < a.P) sc[(size_t)row * a.P + col] = to_16bit<DT>(acc[i][j][e]);
-          }
-        }
+      for (int it = 0; it < BM * CPR / NT; ++it) {
+        const int c = tid + it * NT;
+        const int r = c / CPR, cc = c % CPR;
+        const int row = m0 + r, col = n0 + cc * 8;
+        if (row < a.D && col < a.P)   // P is a multiple of 8 on this path: a chunk is all in or all out
+          *(u32x4_t*)(sc + (size_t)row * a.P + col) = *(const u32x4_t*)(lds + r * EP + cc * 8);
+      }
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i) {
+      const int row = row_base + i * 32;
+      if (row >= a.D) continue;
+      float* prow = a.out + (size_t)row * a.P;
 #pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const int col = col_base + j * 32;
+      for (int j = 0; j < FN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = row_base + i * 32 + 8 * (e >> 2) + (e & 3);
-          if (row < a.D && col < a.P) a.out[(size_t)row * a.P + col] = acc[i][j][e];
+        for (int q = 0; q < 4; ++q) {
+          const int col = col_base + j * 32 + 8 * q;
+          if (col < a.P)
+            *(float4*)(prow + col) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
         }
-      }
+    }
   }
 }
 
