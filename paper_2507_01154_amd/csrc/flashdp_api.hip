@@ -46,8 +46,9 @@ inline size_t elt_bytes(int dtype) { return dtype == FLASHDP_F32 ? 4 : 2; }
 using Cfg256x4 = TileCfg<256, 256, 64, 2, 2>;   // 4 waves, 128x128 per wave
 using Cfg256x8 = TileCfg<256, 256, 64, 2, 4>;   // 8 waves, 128x64 per wave
 using Cfg128x4 = TileCfg<128, 128, 64, 2, 2>;   // 4 waves, 64x64 per wave
+using Cfg256x8k32 = TileCfg<256, 256, 32, 2, 4>; // 8 waves, 32-deep k-tiles (half the LDS)
 
-enum Path { PATH_SIMPLE = 0, PATH_256x4 = 1, PATH_256x8 = 2, PATH_128x4 = 3 };
+enum Path { PATH_SIMPLE = 0, PATH_256x4 = 1, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4 };
 
 struct Plan {
   Path path;
@@ -116,6 +117,7 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& a, hipStream_t st) {
       case PATH_256x4: return launch_mfma<Cfg256x4, MODE, DT>(a, st);
       case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
+      case PATH_256x8k32: return launch_mfma<Cfg256x8k32, MODE, DT>(a, st);
       default: break;
     }
   }

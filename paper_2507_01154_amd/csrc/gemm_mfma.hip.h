@@ -56,7 +56,9 @@ struct TileCfg {
   static constexpr int PAD = 32;                               // row stride = 64 bytes mod 256: 4 consecutive rows hit 4 bank windows
   static constexpr int LDA = BM + PAD, LDB = BN + PAD;         // LDS row strides in elements
   static constexpr int A_STAGE = BK * LDA, B_STAGE = BK * LDB; // elements per stage
-  static constexpr int LDS_BYTES = 2 * (A_STAGE + B_STAGE) * 2;
+  static constexpr int OPERAND_BYTES = 2 * (A_STAGE + B_STAGE) * 2;
+  static constexpr int EPILOGUE_BYTES = BM * (BN + 8) * 2 + 64;   // staged 16-bit output tile + per-wave partial sums
+  static constexpr int LDS_BYTES = OPERAND_BYTES > EPILOGUE_BYTES ? OPERAND_BYTES : EPILOGUE_BYTES;
   static constexpr int CA = BK * BM / 8 / NT, CB = BK * BN / 8 / NT;   // 16-byte chunks per thread per k-tile
   static_assert(BK % 16 == 0 && TM % 32 == 0 && TN % 32 == 0, "tile shape");
   static_assert((BK * BM / 8) % NT == 0 && (BK * BN / 8) % NT == 0, "copy shape");

@@ -1,0 +1,98 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (one flashdp_block_dp_grad call over all layers of the workload, caller-owned workspace, schedule
+auto).  The signal (sigma = 0) and the norms are compared with the full fp64 oracle element by element;
+the noise is compared on sampled elements the oracle computes one by one (2^20 random indices plus the
+first and last 4096 of each layer)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flashdp_oracle as O
+import workloads as W
+import paper_2507_01154_amd as F
+from gpu_util import DEV, rel_fro, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def run_workload(w, sigma, schedule="auto"):
+    layers, host = [], []
+    for l, spec in enumerate(w.layers):
+        X, dY = W.make_layer(w, l)
+        out = torch.full((spec.d_out, spec.d_in), float("nan"), device=DEV)
+        norms = torch.full((w.B,), float("nan"), device=DEV)
+        layers.append(dict(X=to_device(X), dY=to_device(dY), d_in=spec.d_in, d_out=spec.d_out, C=w.C, sigma=sigma,
+                           seed=w.layer_seed(l), layer=l, out_grad=out, out_norms=norms))
+        host.append((X, dY))
+    arr = F.make_layers(layers)
+    dt = F.BF16 if w.dtype == "bf16" else F.F32
+    ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dt, "scratch"), dtype=torch.uint8, device=DEV)
+    F.flashdp_block_dp_grad(arr, w.B, w.T, dt, schedule, ws)
+    torch.cuda.synchronize()
+    used = F.flashdp_last_schedule()
+    outs = [(L["out_grad"].cpu().numpy(), L["out_norms"].cpu().numpy()) for L in layers]
+    return host, outs, used
+
+
+def check_layer(w, l, X, dY, got0, gn, got1, used):
+    spec = w.layers[l]
+    S = spec.d_in * spec.d_out
+    sig, wn = O.linear_dp_grad(X, dY, w.C, 0.0, w.layer_seed(l), l)
+    e_sig = rel_fro(got0, sig)
+    e_norm = float(np.max(np.abs(gn - wn) / wn))
+    tol = 1e-2 if w.dtype == "bf16" else 1e-4
+    tight = 4e-3 if (w.dtype == "bf16" and used == "scratch") else 5e-5
+    assert e_sig <= tol and e_sig <= tight, (spec.name, e_sig)
+    assert e_norm <= 5e-3 and e_norm <= 1e-4, (spec.name, e_norm)
+    rng = np.random.default_rng(100 + l)
+    idx = np.unique(np.concatenate([np.arange(min(4096, S)), np.arange(max(0, S - 4096), S),
+                                    rng.integers(0, S, size=1 << 20)]))
+    z = O.noise_at(w.layer_seed(l), l, idx)
+    scale = w.sigma * w.C
+    d = got1.reshape(-1)[idx].astype(np.float64) - got0.reshape(-1)[idx].astype(np.float64)
+    assert np.max(np.abs(d - scale * z)) <= 4e-6 * scale, spec.name
+    want1 = sig.reshape(-1)[idx] + scale * z
+    assert np.linalg.norm(got1.reshape(-1)[idx] - want1) / np.linalg.norm(want1) <= tol, spec.name
+    # every clipped norm is at most C
+    c = 1.0 / np.maximum(1.0, gn.astype(np.float64) / w.C)
+    assert np.all(c * gn <= w.C * (1 + 1e-6))
+    print(f"{w.name}/{spec.name}: schedule {used}, signal rel err {e_sig:.2e}, norm rel err {e_norm:.2e}, norms {wn.min():.3g}..{wn.max():.3g}")
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("name", ["gpt2_small_mlp_up", "llama7b_q_proj", "llama13b_up_proj"])
+def test_single_layer_configs_full_size(name):
+    w = W.WORKLOADS[name]
+    host, o0, used = run_workload(w, 0.0)
+    _, o1, _ = run_workload(w, w.sigma)
+    assert used == "scratch"
+    X, dY = host[0]
+    check_layer(w, 0, X, dY, o0[0][0], o0[0][1], o1[0][0], used)
+    assert np.array_equal(o0[0][1], o1[0][1])
+
+
+@pytest.fixture(scope="module")
+def block_runs():
+    w = W.WORKLOADS["llama13b_block"]
+    host, o0, used = run_workload(w, 0.0)
+    _, o1, _ = run_workload(w, w.sigma)
+    return w, host, o0, o1, used
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("l", range(7))
+def test_llama13b_block_full_size(block_runs, l):
+    w, host, o0, o1, used = block_runs
+    assert used == "scratch"
+    X, dY = host[l]
+    check_layer(w, l, X, dY, o0[l][0], o0[l][1], o1[l][0], used)
+
+
+@pytest.mark.timeout(300)
+def test_two_pass_schedule_full_size_llama7b():
+    w = W.WORKLOADS["llama7b_q_proj"]
+    host, o0, used = run_workload(w, 0.0, "twopass")
+    _, o1, _ = run_workload(w, w.sigma, "twopass")
+    assert used == "twopass"
+    X, dY = host[0]
+    check_layer(w, 0, X, dY, o0[0][0], o0[0][1], o1[0][0], used)
