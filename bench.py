@@ -22,6 +22,13 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (average over the launches of one step), scaled by what the same counters read for a 1 GiB copy
+# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Source: profiles/gemm_mfma_spill__llama13b_block.md.
+MEASURED_TRAFFIC = {
+    ("llama13b_block", "scratch"): {"read_bytes": 2.20e9, "write_bytes": 0.725e9},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -146,6 +153,11 @@ def main():
         "launches_per_step": n_launch, "avg_launch_ms": round(ms_contract / n_launch, 4),
         "flops_per_launch": flops / n_launch, "traffic": None,
     }
+    mt = MEASURED_TRAFFIC.get((w.name, used))
+    if mt:
+        roofline["traffic"] = mt["read_bytes"] + mt["write_bytes"]
+        roofline["traffic_detail"] = dict(mt, algorithmic_read_bytes=sum(2.0 * w.B * w.T * (s.d_in + s.d_out) for s in w.layers) / n_launch,
+                                          algorithmic_write_bytes=sum(2.0 * w.B * s.d_in * s.d_out for s in w.layers) / n_launch)
 
     result = {
         "metric": "dp_weight_grad_tflops", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
