@@ -51,7 +51,8 @@ using Cfg256x8k32 = TileCfg<256, 256, 32, 2, 4>; // 8 waves, 32-deep k-tiles (ha
 enum Path { PATH_SIMPLE = 0, PATH_256x4 = 1, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4 };
 
 struct Plan {
-  Path path;
+  Path path;         // per-sample passes (norm, spill)
+  Path accum_path;   // batch-accumulating pass (second pass of the two-pass schedule, plain gradient)
   int bm, bn;
   int tiles_m, tiles_n;
 };
@@ -64,19 +65,23 @@ int env_int(const char* name, int dflt) {
 Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
   Plan p;
   const bool mfma_ok = dtype != FLASHDP_F32 && P % 8 == 0 && D % 8 == 0 &&
-                       (T + 64) * (P > D ? P : D) * 2 < (int64_t(1) << 31);
+                       (T + 192) * (P > D ? P : D) * 2 < (int64_t(1) << 31);   // incl. two parked prefetches past the end
   if (!mfma_ok) {
-    p.path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
+    p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
     int choice = env_int("FLASHDP_TILE", 0);
     if (choice == 0) {
       // enough 256x256 work items to fill 256 CUs a few times over, else the smaller tile.
-      // Measured on MI355X (Llama-13B up_proj, B = 8): 8 waves of 128x64 reach 1.09 PFLOP/s in the
-      // norm pass, 4 waves of 128x128 0.95 (one wave per SIMD hides less LDS/barrier latency).
+      // Measured on MI355X (Llama-13B up_proj, B = 8, norm pass): 8 waves of 128x64 with 32-deep k-tiles
+      // 1.16 PFLOP/s, with 64-deep k-tiles 1.05-1.10, 4 waves of 128x128 0.96 (one wave per SIMD hides
+      // less latency and spills).
       const int64_t items = ((D + 255) / 256) * ((P + 255) / 256) * B;
-      choice = items >= 1024 ? PATH_256x8 : PATH_128x4;
+      choice = items >= 1024 ? PATH_256x8k32 : PATH_128x4;
     }
     p.path = (Path)choice;
+    // The long K = B*T loop of the accumulating pass runs faster with 64-deep k-tiles (measured: 1.06 vs
+    // 0.94 PFLOP/s on up_proj), the per-sample passes with 32-deep ones (1.19 vs 1.10); same 256x256 tiling.
+    p.accum_path = (env_int("FLASHDP_TILE", 0) == 0 && p.path == PATH_256x8k32) ? PATH_256x8 : p.path;
     p.bm = p.bn = (p.path == PATH_128x4) ? 128 : 256;
   }
   p.tiles_m = (int)((D + p.bm - 1) / p.bm);
@@ -113,7 +118,7 @@ hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
 template <int MODE, int DT>
 hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& a, hipStream_t st) {
   if constexpr (DT != DT_F32) {
-    switch (p.path) {
+    switch (MODE == MODE_ACCUM ? p.accum_path : p.path) {
       case PATH_256x4: return launch_mfma<Cfg256x4, MODE, DT>(a, st);
       case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);

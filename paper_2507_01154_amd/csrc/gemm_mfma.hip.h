@@ -24,7 +24,36 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace flashdp {
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// Issue-order hints for one phase of the main loop: after each matrix-core instruction, let its share of
+// the phase's LDS reads / LDS writes / global loads issue (they run in the shadow of the 32-cycle MFMA).
+template <int I, int N_MMA, int N_RD, int N_WR, int N_VM>
+__device__ __forceinline__ void sched_interleave() {
+  if constexpr (I < N_MMA) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    constexpr int rd = (N_RD + N_MMA - 1 - I) / N_MMA;
+    constexpr int wr = (N_WR + N_MMA - 1 - I) / N_MMA;
+    constexpr int vm = (N_VM + N_MMA - 1 - I) / N_MMA;
+    if constexpr (rd > 0) __builtin_amdgcn_sched_group_barrier(0x100, rd, 0);
+    if constexpr (wr > 0) __builtin_amdgcn_sched_group_barrier(0x200, wr, 0);
+    if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(0x020, vm, 0);
+    sched_interleave<I + 1, N_MMA, N_RD, N_WR, N_VM>();
+  }
+}
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
@@ -167,16 +196,23 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
   const int nk = kt_per_sample * n_samples;
 
   u32x4_t ra[CA], rb[CB];
-  auto load_global = [&](int k) {
-    const int s = k / kt_per_sample, kt = k - s * kt_per_sample;
-    const char* pa = (const char*)a.dY + (size_t)(sample0 + s) * a_bytes;
-    const char* pb = (const char*)a.X + (size_t)(sample0 + s) * b_bytes;
+  // Fetch cursor: (sample, k-tile) of the next tile to load.  Past the last tile it parks on the last
+  // sample with k-tile index >= kt_per_sample, where every row is >= T and the buffer loads return zeros,
+  // so the main loop can prefetch unconditionally (no branches in its body).
+  int ld_s = 0, ld_kt = 0;
+  auto load_global = [&]() {
+    const char* pa = (const char*)a.dY + (size_t)(sample0 + ld_s) * a_bytes;
+    const char* pb = (const char*)a.X + (size_t)(sample0 + ld_s) * b_bytes;
     const __amdgpu_buffer_rsrc_t rsa = make_rsrc(pa, a_bytes), rsb = make_rsrc(pb, b_bytes);
-    const uint32_t ao = a_off0 + (uint32_t)kt * a_kstep, bo = b_off0 + (uint32_t)kt * b_kstep;
+    const uint32_t ao = a_off0 + (uint32_t)ld_kt * a_kstep, bo = b_off0 + (uint32_t)ld_kt * b_kstep;
 #pragma unroll
     for (int j = 0; j < CA; ++j) ra[j] = __builtin_amdgcn_raw_buffer_load_b128(rsa, (int)(ao + j * a_rstep), 0, 0);
 #pragma unroll
     for (int j = 0; j < CB; ++j) rb[j] = __builtin_amdgcn_raw_buffer_load_b128(rsb, (int)(bo + j * b_rstep), 0, 0);
+    ld_kt += 1;
+    const bool wrap = ld_kt >= kt_per_sample && ld_s + 1 < n_samples;
+    ld_s = wrap ? ld_s + 1 : ld_s;
+    ld_kt = wrap ? 0 : ld_kt;
   };
   auto store_lds = [&](int stage) {
     unsigned short* pa = As + stage * Cfg::A_STAGE + a_lds_w;
@@ -224,34 +260,34 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
     }
   };
 
-  load_global(0);
+  load_global();
   store_lds(0);
-  if (nk > 1) load_global(1);
+  load_global();
   __syncthreads();
   load_frags(0, 0, fa[0], fb[0]);
 
+  constexpr int N_MMA = FM * FN, N_RD = 2 * (FM + FN);
   for (int k = 0; k < nk; ++k) {
     const int cur = k & 1;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int cb = ks & 1, nb = cb ^ 1;
-      if (ks + 1 < KS) {
+    static_for<KS>([&](auto ks_c) {
+      constexpr int ks = decltype(ks_c)::value;
+      constexpr int cb = ks & 1, nb = cb ^ 1;
+      constexpr bool do_store = ks == (KS >= 4 ? KS / 2 - 1 : 0);
+      constexpr bool do_fetch = ks == KS - 2;
+      if constexpr (ks + 1 < KS) {
         load_frags(cur, ks + 1, fa[nb], fb[nb]);
       } else {
         __syncthreads();   // tile k+1 is in LDS, and every wave has read the last fragments of tile k
-        if (k + 1 < nk) load_frags(cur ^ 1, 0, fa[nb], fb[nb]);
+        load_frags(cur ^ 1, 0, fa[nb], fb[nb]);
       }
-      if (ks == (KS >= 4 ? KS / 2 - 1 : 0)) {
-        if (k + 1 < nk) store_lds(cur ^ 1);      // hand the prefetched tile to the other stage
-      }
-      if (ks == KS - 2) {
-        if (k + 2 < nk) load_global(k + 2);      // and start the next fetch into the freed registers
-      }
+      if constexpr (do_store) store_lds(cur ^ 1);      // hand the prefetched tile to the other stage
+      if constexpr (do_fetch) load_global();           // and start the next fetch into the freed registers
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = mfma32<DT>(fb[cb][j], fa[cb][i], acc[i][j]);
-    }
+      sched_interleave<0, N_MMA, N_RD, do_store ? CA + CB : 0, do_fetch ? CA + CB : 0>();
+    });
     if constexpr (MODE == MODE_ACCUM) {
       // sample boundary: rescale so that acc always holds sum_{j<=i} (c_j / c_i) G_j; exact up to one
       // fp32 rounding per boundary, and needs no second set of accumulators
