@@ -54,11 +54,23 @@ __device__ __forceinline__ void widen8(const u32x4_t v, float* f) {
 // out[e] = sum_i c_i * scratch[i][e] + noise_scale * z[e], 8 consecutive elements per thread
 // (16-byte loads from the 16-bit scratch, two Philox groups, two 16-byte stores).  n8 = S / 8.
 template <int DT>
+__device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch, const float* __restrict__ factors, int B,
+                                                size_t S, size_t v, float noise_scale, uint64_t seed, uint32_t layer,
+                                                float* __restrict__ out);
+
+template <int DT>
 __global__ __launch_bounds__(256) void aggregate16_kernel(const void* __restrict__ scratch, const float* __restrict__ factors,
                                                           int B, size_t S, size_t n8, float noise_scale, uint64_t seed,
                                                           uint32_t layer, float* __restrict__ out) {
   const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (v >= n8) return;
+  aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out);
+}
+
+template <int DT>
+__device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch, const float* __restrict__ factors, int B,
+                                                size_t S, size_t v, float noise_scale, uint64_t seed, uint32_t layer,
+                                                float* __restrict__ out) {
   float acc[8];
 #pragma unroll
   for (int q = 0; q < 8; ++q) acc[q] = 0.0f;

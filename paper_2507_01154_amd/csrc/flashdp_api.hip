@@ -70,6 +70,7 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
     int choice = env_int("FLASHDP_TILE", 0);
+    if (choice < 0 || choice > PATH_256x8k32) choice = 0;
     if (choice == 0) {
       // enough 256x256 work items to fill 256 CUs a few times over, else the smaller tile.
       // Measured on MI355X (Llama-13B up_proj, B = 8, norm pass): 8 waves of 128x64 with 32-deep k-tiles

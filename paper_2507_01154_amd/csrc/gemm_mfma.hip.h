@@ -76,8 +76,10 @@ struct GemmArgs {
   float* out;            // [D][P] (ACCUM)
 };
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int WAVES_PER_EU_ = 0>
 struct TileCfg {
+  // waves per SIMD the register allocation must allow (0: whatever one workgroup per CU needs)
+  static constexpr int WAVES_PER_EU = WAVES_PER_EU_ ? WAVES_PER_EU_ : (WAVES_M_ * WAVES_N_ + 3) / 4;
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NT = 64 * WAVES_M * WAVES_N;
   static constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;   // per-wave tile
@@ -156,7 +158,7 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 }
 
 template <typename Cfg, int MODE, int DT>
-__global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(const GemmArgs a) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NT = Cfg::NT;
   constexpr int FM = Cfg::FM, FN = Cfg::FN, LDA = Cfg::LDA, LDB = Cfg::LDB;
   constexpr int CA = Cfg::CA, CB = Cfg::CB;
