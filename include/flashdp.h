@@ -101,6 +101,18 @@ int flashdp_linear_dp_grad(const void* X, const void* dY, int64_t B, int64_t T, 
 int flashdp_block_dp_grad(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
                           int schedule, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Micro-batch form of flashdp_block_dp_grad for gradient accumulation (the paper's micro-batch experiment,
+ * Appendix D.1: several micro-batches per optimizer step).  Per-sample clipping does not depend on how
+ * the batch is split, so calling this once per micro-batch with
+ *     accumulate = 0 on the first micro-batch (out_grad overwritten), 1 on the later ones (added to), and
+ *     add_noise  = 1 on the last micro-batch only (sigma*C*z added once per accumulated batch)
+ * gives the result of one flashdp_block_dp_grad call on the concatenated batch, up to fp32 summation
+ * order.  out_norms receives the norms of this micro-batch's samples.  accumulate = 0, add_noise = 1 is
+ * flashdp_block_dp_grad itself. */
+int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                                int schedule, void* workspace, size_t workspace_bytes, void* stream,
+                                int accumulate, int add_noise);
+
 /* Bytes of workspace the given schedule needs for these layers (the maximum over layers).  Returns 0 on
  * invalid arguments. */
 size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,

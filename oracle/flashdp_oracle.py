@@ -196,6 +196,25 @@ def linear_dp_grad(X, dY, C: float, sigma: float, seed: int, layer: int = 0):
     return out, norms
 
 
+def accumulated_dp_grad(micro_batches, C: float, sigma: float, seed: int, layer: int = 0):
+    """Gradient accumulation over micro-batches (the setting of the paper's micro-batch table, Appendix D.1;
+    the paper does not write the rule out).  Reading: every sample is clipped by its own norm as in
+    stages 1-3, the clipped gradients of all micro-batches are summed, and the noise of stage 4 is added
+    once for the accumulated batch.
+
+    micro_batches: iterable of (X [b,T,P], dY [b,T,D]).  Returns (out [D,P], list of norms per micro-batch)."""
+    out = None
+    all_norms = []
+    for X, dY in micro_batches:
+        part, norms = linear_dp_grad(X, dY, C, 0.0, seed, layer)     # stages 1-3 and the clipped sum, no noise
+        out = part if out is None else out + part
+        all_norms.append(norms)
+    if sigma != 0.0:
+        D, P = out.shape
+        out = out + (float(sigma) * float(C)) * noise_field(seed, layer, D * P).reshape(D, P)
+    return out, all_norms
+
+
 def block_dp_grad(layers):
     """Per-layer clipping over several linears (Algorithm "Per-Layer Gradient Processing",
     Appendix A.1): each layer is processed on its own with its own (C, sigma, seed, layer).

@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.flashdp_linear_dp_grad.restype = ci
         L.flashdp_block_dp_grad.argtypes = [lp, ci, i64, i64, ci, ci, vp, sz, vp]
         L.flashdp_block_dp_grad.restype = ci
+        L.flashdp_block_dp_grad_micro.argtypes = [lp, ci, i64, i64, ci, ci, vp, sz, vp, ci, ci]
+        L.flashdp_block_dp_grad_micro.restype = ci
         L.flashdp_workspace_bytes.argtypes = [lp, ci, i64, i64, ci, ci]
         L.flashdp_workspace_bytes.restype = sz
         L.flashdp_plain_grad.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, vp]
@@ -194,6 +196,16 @@ def flashdp_block_dp_grad(layers, B: int, T: int, dtype: int, schedule=SCHEDULE_
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().flashdp_block_dp_grad(arr, len(arr), B, T, int(dtype), schedule_code(schedule), ws_ptr, ws_bytes,
                                        _stream_handle(stream)), "flashdp_block_dp_grad")
+
+
+def flashdp_block_dp_grad_micro(layers, B: int, T: int, dtype: int, schedule=SCHEDULE_AUTO, workspace=None, stream=None,
+                                accumulate: bool = False, add_noise: bool = True):
+    arr = layers if not isinstance(layers, (list, tuple)) else make_layers(layers)
+    ws_ptr = _ptr(workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().flashdp_block_dp_grad_micro(arr, len(arr), B, T, int(dtype), schedule_code(schedule), ws_ptr, ws_bytes,
+                                             _stream_handle(stream), int(bool(accumulate)), int(bool(add_noise))),
+           "flashdp_block_dp_grad_micro")
 
 
 def flashdp_plain_grad(X, dY, B: int, T: int, d_in: int, d_out: int, dtype: int, out_grad, stream=None):

@@ -56,24 +56,29 @@ __device__ __forceinline__ void widen8(const u32x4_t v, float* f) {
 template <int DT>
 __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch, const float* __restrict__ factors, int B,
                                                 size_t S, size_t v, float noise_scale, uint64_t seed, uint32_t layer,
-                                                float* __restrict__ out);
+                                                float* __restrict__ out, int accumulate);
 
 template <int DT>
 __global__ __launch_bounds__(256) void aggregate16_kernel(const void* __restrict__ scratch, const float* __restrict__ factors,
                                                           int B, size_t S, size_t n8, float noise_scale, uint64_t seed,
-                                                          uint32_t layer, float* __restrict__ out) {
+                                                          uint32_t layer, float* __restrict__ out, int accumulate) {
   const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (v >= n8) return;
-  aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out);
+  aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
 }
 
 template <int DT>
 __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch, const float* __restrict__ factors, int B,
                                                 size_t S, size_t v, float noise_scale, uint64_t seed, uint32_t layer,
-                                                float* __restrict__ out) {
+                                                float* __restrict__ out, int accumulate) {
   float acc[8];
 #pragma unroll
   for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
+  if (accumulate) {   // gradient accumulation: continue from the sum of the earlier micro-batches
+    const float4 o0 = ((const float4*)out)[2 * v], o1 = ((const float4*)out)[2 * v + 1];
+    acc[0] = o0.x; acc[1] = o0.y; acc[2] = o0.z; acc[3] = o0.w;
+    acc[4] = o1.x; acc[5] = o1.y; acc[6] = o1.z; acc[7] = o1.w;
+  }
   const u32x4_t* src = (const u32x4_t*)scratch + v;
   const size_t stride = S / 8;
   for (int i = 0; i < B; ++i) {
@@ -101,10 +106,15 @@ __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch
 template <int DT>
 __global__ __launch_bounds__(256) void aggregate_generic_kernel(const void* __restrict__ scratch, const float* __restrict__ factors,
                                                                 int B, size_t S, float noise_scale, uint64_t seed,
-                                                                uint32_t layer, float* __restrict__ out) {
+                                                                uint32_t layer, float* __restrict__ out, int accumulate) {
   const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (4 * g >= S) return;
   float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (accumulate) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (4 * g + q < S) acc[q] = out[4 * g + q];
+  }
   for (int i = 0; i < B; ++i) {
     const float c = factors[i];
 #pragma unroll

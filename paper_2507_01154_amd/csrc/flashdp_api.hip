@@ -143,23 +143,23 @@ hipError_t launch_gemm(const Plan& p, int dtype, const GemmArgs& a, hipStream_t 
 }
 
 hipError_t launch_aggregate(int dtype, const void* scratch, const float* factors, int B, size_t S, float noise_scale,
-                            uint64_t seed, uint32_t layer, float* out, hipStream_t st) {
+                            uint64_t seed, uint32_t layer, float* out, int accumulate, hipStream_t st) {
   if (dtype != FLASHDP_F32 && S % 8 == 0) {
     const size_t n8 = S / 8;
     const unsigned grid = (unsigned)((n8 + 255) / 256);
     if (dtype == FLASHDP_BF16)
-      hipLaunchKernelGGL((aggregate16_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out);
+      hipLaunchKernelGGL((aggregate16_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
     else
-      hipLaunchKernelGGL((aggregate16_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out);
+      hipLaunchKernelGGL((aggregate16_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
   } else {
     const size_t groups = (S + 3) / 4;
     const unsigned grid = (unsigned)((groups + 255) / 256);
     if (dtype == FLASHDP_BF16)
-      hipLaunchKernelGGL((aggregate_generic_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out);
+      hipLaunchKernelGGL((aggregate_generic_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
     else if (dtype == FLASHDP_F16)
-      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out);
+      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
     else
-      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F32>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out);
+      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F32>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
   }
   return hipGetLastError();
 }
@@ -231,7 +231,8 @@ size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype,
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; } } while (0)
 
 // Enqueues Algorithm 1 for one layer.
-int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool use_scratch, char* ws, hipStream_t st) {
+int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool use_scratch, char* ws, hipStream_t st,
+              bool accumulate, bool add_noise) {
   const int stages = g_ctx.stages;
   const int64_t P = L.d_in, D = L.d_out;
   const Plan plan = make_plan(B, T, P, D, dtype);
@@ -245,9 +246,10 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool us
   float* factors = reinterpret_cast<float*>(ws + wl.factors);
   a.factors = factors;
   a.out = L.out_grad;
+  a.accumulate = accumulate ? 1 : 0;
   const int tiles = plan.tiles_m * plan.tiles_n;
   const size_t S = (size_t)D * P;
-  const float noise_scale = L.sigma * L.C;
+  const float noise_scale = add_noise ? L.sigma * L.C : 0.0f;
 
   if (use_scratch) {
     if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_SPILL>(plan, dtype, a, st));
@@ -256,7 +258,7 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool us
       HIP_TRY(hipGetLastError());
     }
     if (stages & FLASHDP_STAGE_AGGREGATE)
-      HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, st));
+      HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0, st));
   } else {
     if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
     if (stages & FLASHDP_STAGE_CLIP) {
@@ -277,8 +279,9 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool us
 
 extern "C" {
 
-int flashdp_block_dp_grad(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
-                          int schedule, void* workspace, size_t workspace_bytes, void* stream) {
+int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                                int schedule, void* workspace, size_t workspace_bytes, void* stream,
+                                int accumulate, int add_noise) {
   if (!layers || n_layers <= 0 || !valid_dtype(dtype) || !valid_schedule(schedule)) return FLASHDP_INVALID_ARGUMENT;
   for (int l = 0; l < n_layers; ++l) {
     int st = check_layer(layers[l], B, T);
@@ -315,11 +318,16 @@ int flashdp_block_dp_grad(const flashdp_layer_t* layers, int n_layers, int64_t B
     ws = static_cast<char*>(p);
   }
   for (int l = 0; l < n_layers; ++l) {
-    st = run_layer(layers[l], B, T, dtype, use_scratch, ws, static_cast<hipStream_t>(stream));
+    st = run_layer(layers[l], B, T, dtype, use_scratch, ws, static_cast<hipStream_t>(stream), accumulate != 0, add_noise != 0);
     if (st != FLASHDP_OK) return st;
   }
   g_ctx.last_schedule = use_scratch ? "scratch" : "twopass";
   return FLASHDP_OK;
+}
+
+int flashdp_block_dp_grad(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                          int schedule, void* workspace, size_t workspace_bytes, void* stream) {
+  return flashdp_block_dp_grad_micro(layers, n_layers, B, T, dtype, schedule, workspace, workspace_bytes, stream, 0, 1);
 }
 
 int flashdp_linear_dp_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
@@ -353,7 +361,7 @@ int flashdp_plain_grad(const void* X, const void* dY, int64_t B, int64_t T, int6
   GemmArgs a;
   a.X = X; a.dY = dY; a.B = (int)B; a.T = (int)T; a.P = (int)d_in; a.D = (int)d_out;
   a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
-  a.partials = nullptr; a.scratch = nullptr; a.factors = nullptr; a.out = out_grad;
+  a.partials = nullptr; a.scratch = nullptr; a.factors = nullptr; a.out = out_grad; a.accumulate = 0;
   HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, static_cast<hipStream_t>(stream)));
   return FLASHDP_OK;
 }

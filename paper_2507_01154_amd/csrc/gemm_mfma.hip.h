@@ -74,6 +74,7 @@ struct GemmArgs {
   void* scratch;         // [B][D][P] 16-bit (SPILL)
   const float* factors;  // [B] clip factors (ACCUM); nullptr = all ones
   float* out;            // [D][P] (ACCUM)
+  int accumulate;        // ACCUM: add to what out holds (gradient accumulation over micro-batches) instead of overwriting
 };
 
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int WAVES_PER_EU_ = 0>
@@ -373,8 +374,14 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int col = col_base + j * 32 + 8 * q;
-          if (col < a.P)
-            *(float4*)(prow + col) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          if (col < a.P) {
+            float4 v = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            if (a.accumulate) {
+              const float4 o = *(const float4*)(prow + col);
+              v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+            }
+            *(float4*)(prow + col) = v;
+          }
         }
     }
   }

@@ -116,7 +116,10 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int row = m0 + 4 * ty + i, col = n0 + 4 * tx + j;
-        if (row < a.D && col < a.P) a.out[(size_t)row * a.P + col] = tot[i][j];
+        if (row < a.D && col < a.P) {
+          float* po = a.out + (size_t)row * a.P + col;
+          *po = a.accumulate ? *po + tot[i][j] : tot[i][j];
+        }
       }
   }
 }

@@ -259,3 +259,40 @@ def test_block_variant_matches_layerwise_oracle():
             got = layers[l]["out_grad"].cpu().numpy()
             assert rel_fro(got - w.sigma * w.C * z, sig) <= tight_tol("bf16", schedule) + 1e-4   # fp32 cancellation of the noise
             assert np.max(np.abs(layers[l]["out_norms"].cpu().numpy() - wn) / wn) <= 1e-4
+
+
+@pytest.mark.parametrize("schedule", ["scratch", "twopass"])
+@pytest.mark.parametrize("shape", [(6, 96, 264, 392), (5, 40, 77, 131)])
+def test_gradient_accumulation_over_micro_batches(schedule, shape):
+    B, T, P, D = shape
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    split = [2, 1, B - 3]
+    idx = np.cumsum([0] + split)
+    mbs = [(X[a:b], dY[a:b]) for a, b in zip(idx[:-1], idx[1:])]
+    sigma, seed, layer = 0.9, 21, 4
+    want0, wn = O.accumulated_dp_grad(mbs, 1.0, 0.0, seed, layer)
+    z = O.noise_field(seed, layer, D * P).reshape(D, P)
+    out = torch.full((D, P), float("nan"), device=DEV)
+    res = {}
+    for sg in (0.0, sigma):
+        got_norms = []
+        for k, (xm, ym) in enumerate(mbs):
+            b = xm.shape[0]
+            norms = torch.full((b,), float("nan"), device=DEV)
+            L = [dict(X=to_device(xm), dY=to_device(ym), d_in=P, d_out=D, C=1.0, sigma=sg, seed=seed, layer=layer,
+                      out_grad=out, out_norms=norms)]
+            F.flashdp_block_dp_grad_micro(L, b, T, F.BF16, schedule, accumulate=(k > 0), add_noise=(k == len(mbs) - 1))
+            torch.cuda.synchronize()
+            got_norms.append(norms.cpu().numpy())
+        res[sg] = out.cpu().numpy().copy()
+        for g, wv in zip(got_norms, wn):
+            assert np.max(np.abs(g - wv) / wv) <= 1e-4
+    assert rel_fro(res[0.0], want0) <= tight_tol("bf16", schedule)
+    d = res[sigma].astype(np.float64) - res[0.0].astype(np.float64)
+    assert np.max(np.abs(d - sigma * z)) <= 4e-6 * sigma * max(1.0, float(np.max(np.abs(res[0.0]))) / sigma)
+    assert rel_fro(res[sigma], want0 + sigma * z) <= 1e-2
+    # and it equals the one-call result on the whole batch up to fp32 summation order
+    whole, _, _ = run_layer(X, dY, 1.0, 0.0, seed, layer, schedule)
+    assert rel_fro(res[0.0], whole.astype(np.float64)) <= 1e-6

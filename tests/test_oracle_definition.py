@@ -249,3 +249,20 @@ def test_workload_generator_recipe():
     b = W.float32_to_bf16_bits(f)
     assert b[0] == 0x3F80 and b[1] == 0x3F80 and b[2] == 0x3F82 and b[3] == 0xBF80
     assert abs(O.widen(b[4:5])[0] - 3.0e-3) <= 2.0 ** -17   # half an ulp in [2^-9, 2^-8)
+
+
+def test_accumulation_over_micro_batches_equals_the_full_batch():
+    # clipping is per sample, so splitting the batch changes nothing; noise enters once
+    X, dY = _rand(6, 5, 4, 3, 31)
+    dY *= np.array([0.01, 30, 0.1, 3, 0.02, 8], np.float32)[:, None, None]
+    full, norms = O.linear_dp_grad(X, dY, 1.0, 0.7, 5, 2)
+    for split in ([2, 4], [1, 2, 3], [6], [3, 3]):
+        idx = np.cumsum([0] + split)
+        mbs = [(X[a:b], dY[a:b]) for a, b in zip(idx[:-1], idx[1:])]
+        acc, nlist = O.accumulated_dp_grad(mbs, 1.0, 0.7, 5, 2)
+        assert np.allclose(acc, full, rtol=1e-12, atol=1e-14)
+        assert np.allclose(np.concatenate(nlist), norms, rtol=1e-14)
+    # noise once, not once per micro-batch
+    a0, _ = O.accumulated_dp_grad([(X[:3], dY[:3]), (X[3:], dY[3:])], 1.0, 0.0, 5, 2)
+    a1, _ = O.accumulated_dp_grad([(X[:3], dY[:3]), (X[3:], dY[3:])], 1.0, 0.7, 5, 2)
+    assert np.allclose(a1 - a0, 0.7 * O.noise_field(5, 2, 12).reshape(3, 4), rtol=1e-12, atol=1e-14)
