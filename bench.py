@@ -36,7 +36,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama13b_block")
-    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch"])
+    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch", "explicit"])
+    ap.add_argument("--no-schedule-comparison", action="store_true",
+                    help="skip timing the other schedules (two-pass recompute, explicit four-stage) beside the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -126,7 +128,8 @@ def main():
     sched = args.schedule
     ws = None
     if sched != "twopass":
-        ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, "scratch"), dtype=torch.uint8, device=dev)
+        ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, "explicit" if sched == "explicit" else "scratch"),
+                         dtype=torch.uint8, device=dev)
 
     def step():
         F.flashdp_block_dp_grad(arr, w.B, w.T, dtype_code, sched, ws)
@@ -189,6 +192,21 @@ def main():
                            "own_plain_ms": round(ms_own, 4), "own_plain_tflops": round(flops / ms_own / 1e9, 2)}
         result["ratio_vs_nondp"] = round(best / ms, 4)
         # restore the outputs of a full DP step
+        step()
+        torch.cuda.synchronize()
+
+    if not args.no_schedule_comparison:
+        # the same step under the other schedules: two-pass recompute (the paper's "implicit" class) and the
+        # explicit four-stage flow with materialised fp32 per-sample gradients (its "explicit" class)
+        cmp = {used: round(ms, 4)}
+        for other in ("scratch", "twopass", "explicit"):
+            if other in cmp:
+                continue
+            ws_o = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, other), dtype=torch.uint8, device=dev)
+            cmp[other] = round(time_steps(lambda: F.flashdp_block_dp_grad(arr, w.B, w.T, dtype_code, other, ws_o),
+                                          max(3, args.steps // 4), 2), 4)
+            del ws_o
+        result["schedule_ms"] = cmp
         step()
         torch.cuda.synchronize()
 

@@ -68,8 +68,11 @@ enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
  *   SCRATCH  each G_i tile is computed once, its square-sum taken from the fp32 accumulators, the tile
  *            parked in a per-layer scratch (16-bit for 16-bit inputs, fp32 for fp32 inputs), and a
  *            streaming kernel forms sum_i c_i G_i + noise (workspace: B * d_out * d_in elements);
+ *   EXPLICIT the explicit four-stage flow of Appendix B.2, one kernel per stage, the fp32 per-sample
+ *            gradients written to and re-read from HBM between stages (workspace: 4 * B * d_out * d_in
+ *            bytes).  Never chosen by AUTO: it exists to be measured against;
  *   AUTO     SCRATCH when the workspace is large enough, else TWOPASS.                                 */
-enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2 };
+enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2, FLASHDP_SCHEDULE_EXPLICIT = 3 };
 
 /* One linear layer of a block (Appendix A.1, "Per-Layer Gradient Processing": every layer is clipped
  * by its own norm with its own C and sigma). */
@@ -150,7 +153,7 @@ int flashdp_set_stages(int mask);
 /* Frees the library-owned workspaces (synchronises the device first). */
 int flashdp_release(void);
 
-/* Name of the schedule the last call on this thread used: "twopass" or "scratch" ("none" before any). */
+/* Name of the schedule the last call on this thread used: "twopass", "scratch" or "explicit" ("none" before any). */
 const char* flashdp_last_schedule(void);
 
 const char* flashdp_status_string(int status);

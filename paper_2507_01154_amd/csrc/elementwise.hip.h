@@ -143,6 +143,82 @@ __global__ __launch_bounds__(256) void aggregate_generic_kernel(const void* __re
     if (4 * g + q < S) out[4 * g + q] = acc[q];
 }
 
+// ---- the explicit four-stage flow of Appendix B.2 on a materialised fp32 G[B][S] (measured comparison) ----
+
+// Stage 2: per-sample squared norm of G_i read back from HBM.  grid = (chunks, B); every workgroup sums a
+// contiguous chunk of 256 * 4 * ITER elements and writes one partial; clip_factors_kernel finishes.
+__global__ __launch_bounds__(256) void explicit_norm_kernel(const float* __restrict__ G, size_t S, int chunks,
+                                                            float* __restrict__ partials) {
+  __shared__ float red[4];
+  const int i = blockIdx.y, tid = threadIdx.x;
+  const size_t per = (S + chunks - 1) / chunks;
+  const size_t lo = (size_t)blockIdx.x * per, hi = lo + per < S ? lo + per : S;
+  const float* g = G + (size_t)i * S;
+  float ss = 0.0f;
+  for (size_t e = lo + (size_t)tid * 4; e < hi; e += 1024) {
+    if (e + 3 < hi && (((uintptr_t)(g + e)) & 15) == 0) {
+      const float4 v = *(const float4*)(g + e);
+      ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+    } else {
+      for (size_t q = e; q < hi && q < e + 4; ++q) ss = fmaf(g[q], g[q], ss);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  if (tid == 0) partials[(size_t)i * chunks + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// Stage 3: G'_i = c_i * G_i, in place (load G and the factor, store the clipped gradient back to HBM).
+__global__ __launch_bounds__(256) void explicit_clip_kernel(float* __restrict__ G, size_t S, const float* __restrict__ factors) {
+  const int i = blockIdx.y;
+  const float c = factors[i];
+  float* g = G + (size_t)i * S;
+  const size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (e + 3 < S && (((uintptr_t)(g + e)) & 15) == 0) {
+    float4 v = *(float4*)(g + e);
+    v.x *= c; v.y *= c; v.z *= c; v.w *= c;
+    *(float4*)(g + e) = v;
+  } else {
+    for (size_t q = e; q < S && q < e + 4; ++q) g[q] *= c;
+  }
+}
+
+// Stage 4: out = sum_i G'_i + noise (one Philox group of 4 elements per thread).
+__global__ __launch_bounds__(256) void explicit_sum_noise_kernel(const float* __restrict__ G, int B, size_t S, float noise_scale,
+                                                                 uint64_t seed, uint32_t layer, float* __restrict__ out, int accumulate) {
+  const size_t g4 = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t e = g4 * 4;
+  if (e >= S) return;
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  const bool vec = e + 3 < S && (S & 3) == 0;
+  if (accumulate) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (e + q < S) acc[q] = out[e + q];
+  }
+  for (int i = 0; i < B; ++i) {
+    const float* g = G + (size_t)i * S + e;
+    if (vec) {
+      const float4 v = *(const float4*)g;
+      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (e + q < S) acc[q] += g[q];
+    }
+  }
+  if (noise_scale != 0.0f) {
+    const Normals4 z = noise_group(seed, layer, g4);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = fmaf(noise_scale, z.z[q], acc[q]);
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (e + q < S) out[e + q] = acc[q];
+}
+
 // out[e] = (ADD ? out[e] : 0) + scale * z[e]: the noise step alone (second pass of the two-pass schedule,
 // and the stand-alone field for checks).
 template <bool ADD>

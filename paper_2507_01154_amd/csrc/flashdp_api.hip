@@ -38,7 +38,7 @@ std::map<int, OwnedWs> g_owned;   // device -> library-owned workspace
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == FLASHDP_BF16 || d == FLASHDP_F32 || d == FLASHDP_F16; }
-inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_SCRATCH; }
+inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_EXPLICIT; }
 inline size_t elt_bytes(int dtype) { return dtype == FLASHDP_F32 ? 4 : 2; }
 
 // ---- kernel plans --------------------------------------------------------------------------------
@@ -92,12 +92,24 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
 
 struct WsLayout { size_t factors, partials, scratch, total; };
 
-WsLayout ws_layout(const Plan& p, int64_t B, int64_t P, int64_t D, int dtype, bool with_scratch) {
+// Number of squared-norm partials per sample the explicit schedule's norm kernel writes.
+int explicit_chunks(int64_t P, int64_t D) {
+  const int64_t c = ((int64_t)P * D + 16383) / 16384;
+  return (int)(c < 1 ? 1 : (c > 2048 ? 2048 : c));
+}
+
+// mode: FLASHDP_SCHEDULE_TWOPASS (no scratch), _SCRATCH (input-width scratch), _EXPLICIT (fp32 scratch)
+WsLayout ws_layout(const Plan& p, int64_t B, int64_t P, int64_t D, int dtype, int mode) {
   WsLayout w;
   w.factors = 0;
   w.partials = align_up((size_t)B * 4, 256);
-  w.scratch = w.partials + align_up((size_t)B * p.tiles_m * p.tiles_n * 4, 256);
-  w.total = w.scratch + (with_scratch ? align_up((size_t)B * D * P * elt_bytes(dtype), 256) : 0);
+  size_t n_part = (size_t)p.tiles_m * p.tiles_n;
+  if (mode == FLASHDP_SCHEDULE_EXPLICIT) n_part = std::max(n_part, (size_t)explicit_chunks(P, D));
+  w.scratch = w.partials + align_up((size_t)B * n_part * 4, 256);
+  size_t sc = 0;
+  if (mode == FLASHDP_SCHEDULE_SCRATCH) sc = (size_t)B * D * P * elt_bytes(dtype);
+  if (mode == FLASHDP_SCHEDULE_EXPLICIT) sc = (size_t)B * D * P * 4;
+  w.total = w.scratch + align_up(sc, 256);
   return w;
 }
 
@@ -219,30 +231,32 @@ int resolve_schedule(int schedule) {
   if (s && *s) {
     if (!std::strcmp(s, "twopass")) return FLASHDP_SCHEDULE_TWOPASS;
     if (!std::strcmp(s, "scratch")) return FLASHDP_SCHEDULE_SCRATCH;
+    if (!std::strcmp(s, "explicit")) return FLASHDP_SCHEDULE_EXPLICIT;
   }
   return schedule;
 }
 
-size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool with_scratch) {
+size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mode) {
   const Plan p = make_plan(B, T, L.d_in, L.d_out, dtype);
-  return ws_layout(p, B, L.d_in, L.d_out, dtype, with_scratch).total;
+  return ws_layout(p, B, L.d_in, L.d_out, dtype, mode).total;
 }
 
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; } } while (0)
 
 // Enqueues Algorithm 1 for one layer.
-int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool use_scratch, char* ws, hipStream_t st,
+int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mode, char* ws, hipStream_t st,
               bool accumulate, bool add_noise) {
+  const bool use_scratch = mode == FLASHDP_SCHEDULE_SCRATCH;
   const int stages = g_ctx.stages;
   const int64_t P = L.d_in, D = L.d_out;
   const Plan plan = make_plan(B, T, P, D, dtype);
-  const WsLayout wl = ws_layout(plan, B, P, D, dtype, use_scratch);
+  const WsLayout wl = ws_layout(plan, B, P, D, dtype, mode);
   GemmArgs a;
   a.X = L.X; a.dY = L.dY;
   a.B = (int)B; a.T = (int)T; a.P = (int)P; a.D = (int)D;
   a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
   a.partials = reinterpret_cast<float*>(ws + wl.partials);
-  a.scratch = use_scratch ? (void*)(ws + wl.scratch) : nullptr;
+  a.scratch = mode != FLASHDP_SCHEDULE_TWOPASS ? (void*)(ws + wl.scratch) : nullptr;
   float* factors = reinterpret_cast<float*>(ws + wl.factors);
   a.factors = factors;
   a.out = L.out_grad;
@@ -251,7 +265,26 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, bool us
   const size_t S = (size_t)D * P;
   const float noise_scale = add_noise ? L.sigma * L.C : 0.0f;
 
-  if (use_scratch) {
+  if (mode == FLASHDP_SCHEDULE_EXPLICIT) {
+    // The explicit four-stage flow of Appendix B.2, every stage a kernel of its own with the fp32
+    // per-sample gradients going through HBM in between: the comparison the fused schedules are measured against.
+    float* G = reinterpret_cast<float*>(a.scratch);
+    const int chunks = explicit_chunks(P, D);
+    if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_MATERIALIZE>(plan, dtype, a, st));      // stage 1
+    if (stages & FLASHDP_STAGE_CLIP) {
+      hipLaunchKernelGGL(explicit_norm_kernel, dim3((unsigned)chunks, (unsigned)B), dim3(256), 0, st, G, S, chunks, a.partials);   // stage 2
+      HIP_TRY(hipGetLastError());
+      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, chunks, L.C, factors, L.out_norms);
+      HIP_TRY(hipGetLastError());
+      hipLaunchKernelGGL(explicit_clip_kernel, dim3((unsigned)((S / 4 + 256) / 256), (unsigned)B), dim3(256), 0, st, G, S, factors);  // stage 3
+      HIP_TRY(hipGetLastError());
+    }
+    if (stages & FLASHDP_STAGE_AGGREGATE) {
+      hipLaunchKernelGGL(explicit_sum_noise_kernel, dim3((unsigned)(((S + 3) / 4 + 255) / 256)), dim3(256), 0, st, G, (int)B, S, noise_scale,
+                         L.seed, L.layer, L.out_grad, accumulate ? 1 : 0);                                                             // stage 4
+      HIP_TRY(hipGetLastError());
+    }
+  } else if (use_scratch) {
     if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_SPILL>(plan, dtype, a, st));
     if (stages & FLASHDP_STAGE_CLIP) {
       hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
@@ -289,39 +322,38 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
   }
   if (workspace && !aligned16(workspace)) return FLASHDP_MISALIGNED;
   schedule = resolve_schedule(schedule);
-  size_t need_scratch = 0, need_small = 0;
+  size_t need_scratch = 0, need_small = 0, need_explicit = 0;
   for (int l = 0; l < n_layers; ++l) {
-    need_scratch = std::max(need_scratch, layer_ws_bytes(layers[l], B, T, dtype, true));
-    need_small = std::max(need_small, layer_ws_bytes(layers[l], B, T, dtype, false));
+    need_scratch = std::max(need_scratch, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_SCRATCH));
+    need_small = std::max(need_small, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_TWOPASS));
+    need_explicit = std::max(need_explicit, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_EXPLICIT));
   }
   int dev = 0;
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
   char* ws = static_cast<char*>(workspace);
-  bool use_scratch;
+  int mode;
   if (workspace) {
-    if (schedule == FLASHDP_SCHEDULE_SCRATCH) {
-      if (workspace_bytes < need_scratch) return FLASHDP_WORKSPACE_TOO_SMALL;
-      use_scratch = true;
-    } else if (schedule == FLASHDP_SCHEDULE_TWOPASS) {
-      if (workspace_bytes < need_small) return FLASHDP_WORKSPACE_TOO_SMALL;
-      use_scratch = false;
+    if (schedule == FLASHDP_SCHEDULE_AUTO) {
+      mode = workspace_bytes >= need_scratch ? FLASHDP_SCHEDULE_SCRATCH : FLASHDP_SCHEDULE_TWOPASS;
     } else {
-      use_scratch = workspace_bytes >= need_scratch;
-      if (!use_scratch && workspace_bytes < need_small) return FLASHDP_WORKSPACE_TOO_SMALL;
+      mode = schedule;
     }
+    const size_t need = mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
+    if (workspace_bytes < need) return FLASHDP_WORKSPACE_TOO_SMALL;
   } else {
-    use_scratch = schedule != FLASHDP_SCHEDULE_TWOPASS;
+    mode = schedule == FLASHDP_SCHEDULE_AUTO ? FLASHDP_SCHEDULE_SCRATCH : schedule;
+    const size_t need = mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
     void* p = nullptr; size_t got = 0;
-    st = owned_workspace(use_scratch ? need_scratch : need_small, &p, &got);
+    st = owned_workspace(need, &p, &got);
     if (st != FLASHDP_OK) return st;
     ws = static_cast<char*>(p);
   }
   for (int l = 0; l < n_layers; ++l) {
-    st = run_layer(layers[l], B, T, dtype, use_scratch, ws, static_cast<hipStream_t>(stream), accumulate != 0, add_noise != 0);
+    st = run_layer(layers[l], B, T, dtype, mode, ws, static_cast<hipStream_t>(stream), accumulate != 0, add_noise != 0);
     if (st != FLASHDP_OK) return st;
   }
-  g_ctx.last_schedule = use_scratch ? "scratch" : "twopass";
+  g_ctx.last_schedule = mode == FLASHDP_SCHEDULE_SCRATCH ? "scratch" : mode == FLASHDP_SCHEDULE_EXPLICIT ? "explicit" : "twopass";
   return FLASHDP_OK;
 }
 
@@ -343,7 +375,7 @@ size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int6
   size_t need = 0;
   for (int l = 0; l < n_layers; ++l) {
     if (check_dims(B, T, layers[l].d_in, layers[l].d_out) != FLASHDP_OK) return 0;
-    need = std::max(need, layer_ws_bytes(layers[l], B, T, dtype, schedule != FLASHDP_SCHEDULE_TWOPASS));
+    need = std::max(need, layer_ws_bytes(layers[l], B, T, dtype, schedule == FLASHDP_SCHEDULE_AUTO ? FLASHDP_SCHEDULE_SCRATCH : schedule));
   }
   return need;
 }

@@ -62,7 +62,10 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
-enum : int { MODE_NORM = 0, MODE_SPILL = 1, MODE_ACCUM = 2 };
+// NORM: squared norm only.  SPILL: squared norm + 16-bit tile to the scratch.  ACCUM: sum over the batch with
+// clip factors.  MATERIALIZE: the fp32 per-sample gradient itself to the scratch, nothing else (stage 1 of the
+// explicit four-stage flow of Appendix B.2, built as a measured comparison).
+enum : int { MODE_NORM = 0, MODE_SPILL = 1, MODE_ACCUM = 2, MODE_MATERIALIZE = 3 };
 enum : int { DT_BF16 = 0, DT_F32 = 1, DT_F16 = 2 };
 
 struct GemmArgs {
@@ -71,7 +74,7 @@ struct GemmArgs {
   int B, T, P, D;
   int tiles_m, tiles_n;  // ceil(D / BM), ceil(P / BN)
   float* partials;       // [B][tiles_m * tiles_n] squared-norm partial sums (NORM, SPILL)
-  void* scratch;         // [B][D][P] 16-bit (SPILL)
+  void* scratch;         // [B][D][P] 16-bit (SPILL) or fp32 (MATERIALIZE)
   const float* factors;  // [B] clip factors (ACCUM); nullptr = all ones
   float* out;            // [D][P] (ACCUM)
   int accumulate;        // ACCUM: add to what out holds (gradient accumulation over micro-batches) instead of overwriting
@@ -368,7 +371,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
     for (int i = 0; i < FM; ++i) {
       const int row = row_base + i * 32;
       if (row >= a.D) continue;
-      float* prow = a.out + (size_t)row * a.P;
+      float* obase = a.out;
+      if constexpr (MODE == MODE_MATERIALIZE) obase = (float*)a.scratch + (size_t)sample0 * a.D * a.P;
+      float* prow = obase + (size_t)row * a.P;
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -376,7 +381,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
           const int col = col_base + j * 32 + 8 * q;
           if (col < a.P) {
             float4 v = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-            if (a.accumulate) {
+            if (MODE == MODE_ACCUM && a.accumulate) {
               const float4 o = *(const float4*)(prow + col);
               v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
             }

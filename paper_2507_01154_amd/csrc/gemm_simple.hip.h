@@ -117,8 +117,12 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs a) {
       for (int j = 0; j < 4; ++j) {
         const int row = m0 + 4 * ty + i, col = n0 + 4 * tx + j;
         if (row < a.D && col < a.P) {
-          float* po = a.out + (size_t)row * a.P + col;
-          *po = a.accumulate ? *po + tot[i][j] : tot[i][j];
+          if constexpr (MODE == MODE_MATERIALIZE) {
+            ((float*)a.scratch)[(size_t)sample0 * a.D * a.P + (size_t)row * a.P + col] = acc[i][j];
+          } else {
+            float* po = a.out + (size_t)row * a.P + col;
+            *po = a.accumulate ? *po + tot[i][j] : tot[i][j];
+          }
         }
       }
   }

@@ -96,3 +96,31 @@ def test_two_pass_schedule_full_size_llama7b():
     assert used == "twopass"
     X, dY = host[0]
     check_layer(w, 0, X, dY, o0[0][0], o0[0][1], o1[0][0], used)
+
+
+@pytest.mark.timeout(300)
+def test_explicit_four_stage_schedule_full_size_llama7b():
+    w = W.WORKLOADS["llama7b_q_proj"]
+    host, o0, used = run_workload_sched(w, 0.0, "explicit")
+    _, o1, _ = run_workload_sched(w, w.sigma, "explicit")
+    assert used == "explicit"
+    X, dY = host[0]
+    check_layer(w, 0, X, dY, o0[0][0], o0[0][1], o1[0][0], used)
+
+
+def run_workload_sched(w, sigma, schedule):
+    """run_workload with a workspace sized for the given schedule."""
+    layers, host = [], []
+    for l, spec in enumerate(w.layers):
+        X, dY = W.make_layer(w, l)
+        out = torch.full((spec.d_out, spec.d_in), float("nan"), device=DEV)
+        norms = torch.full((w.B,), float("nan"), device=DEV)
+        layers.append(dict(X=to_device(X), dY=to_device(dY), d_in=spec.d_in, d_out=spec.d_out, C=w.C, sigma=sigma,
+                           seed=w.layer_seed(l), layer=l, out_grad=out, out_norms=norms))
+        host.append((X, dY))
+    arr = F.make_layers(layers)
+    ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, F.BF16, schedule), dtype=torch.uint8, device=DEV)
+    F.flashdp_block_dp_grad(arr, w.B, w.T, F.BF16, schedule, ws)
+    torch.cuda.synchronize()
+    outs = [(L["out_grad"].cpu().numpy(), L["out_norms"].cpu().numpy()) for L in layers]
+    return host, outs, F.flashdp_last_schedule()

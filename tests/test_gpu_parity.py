@@ -30,7 +30,7 @@ TOL_NORM_STATED = 5e-3
 
 
 def tight_tol(dtype, schedule):
-    if dtype == "fp32" or schedule == "twopass":
+    if dtype == "fp32" or schedule in ("twopass", "explicit"):
         return 5e-5
     return 4e-3 if dtype == "bf16" else 6e-4   # f16 keeps 11 significant bits
 
@@ -117,8 +117,8 @@ SMALL = [
 
 
 @pytest.mark.parametrize("shape", SMALL)
-@pytest.mark.parametrize("schedule", ["twopass", "scratch"])
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("schedule", ["twopass", "scratch", "explicit"])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 def test_small_bf16_all_tiles(shape, schedule, tile):
     B, T, P, D = shape
     base = W.WORKLOADS["gpt2_small_mlp_up"]
@@ -128,7 +128,7 @@ def test_small_bf16_all_tiles(shape, schedule, tile):
     print(shape, schedule, tile, e)
 
 
-@pytest.mark.parametrize("schedule", ["twopass", "scratch"])
+@pytest.mark.parametrize("schedule", ["twopass", "scratch", "explicit"])
 def test_odd_dims_take_generic_kernel(schedule):
     base = W.WORKLOADS["gpt2_small_mlp_up"]
     w = W.scaled_down(base, B=3, T=37, dims=[(77, 131)])
@@ -136,7 +136,7 @@ def test_odd_dims_take_generic_kernel(schedule):
     check_case(X, dY, 1.0, 0.5, 5, 1, "bf16", schedule)
 
 
-@pytest.mark.parametrize("schedule", ["twopass", "scratch"])
+@pytest.mark.parametrize("schedule", ["twopass", "scratch", "explicit"])
 @pytest.mark.parametrize("shape", [(3, 100, 136, 264), (2, 33, 50, 70)])
 def test_f16_and_fp32_inputs(schedule, shape):
     B, T, P, D = shape
@@ -209,6 +209,13 @@ def test_repeatable_and_workspace_argument():
     with pytest.raises(F.FlashDPError) as ei:
         run_layer(X, dY, 1.0, 1.0, 7, 1, "scratch", workspace=ws[: need - 256])
     assert ei.value.status == F.WORKSPACE_TOO_SMALL
+    need_x = F.flashdp_workspace_bytes(L, B, T, F.BF16, "explicit")
+    assert need_x >= B * D * P * 4
+    with pytest.raises(F.FlashDPError) as ei:
+        run_layer(X, dY, 1.0, 1.0, 7, 1, "explicit", workspace=ws)          # sized for the 16-bit scratch only
+    assert ei.value.status == F.WORKSPACE_TOO_SMALL
+    e = run_layer(X, dY, 1.0, 1.0, 7, 1, "explicit", workspace=torch.empty(need_x, dtype=torch.uint8, device=DEV))
+    assert e[2] == "explicit" and rel_fro(e[0], a[0].astype(np.float64)) <= 1e-2
 
 
 def test_eleven_argument_entry_point_uses_context():
