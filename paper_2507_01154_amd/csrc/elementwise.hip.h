@@ -185,9 +185,12 @@ __global__ __launch_bounds__(256) void explicit_clip_kernel(float* __restrict__ 
   }
 }
 
-// Stage 4: out = sum_i G'_i + noise (one Philox group of 4 elements per thread).
-__global__ __launch_bounds__(256) void explicit_sum_noise_kernel(const float* __restrict__ G, int B, size_t S, float noise_scale,
-                                                                 uint64_t seed, uint32_t layer, float* __restrict__ out, int accumulate) {
+// Stage 4: out = sum_i G'_i + noise (one Philox group of 4 elements per thread).  With `factors` the clip
+// factor is applied here instead (out = sum_i c_i G_i + noise): the aggregation of the scratch schedule
+// for fp32 inputs, whose scratch is fp32 as well.
+__global__ __launch_bounds__(256) void aggregate32_kernel(const float* __restrict__ G, const float* __restrict__ factors, int B,
+                                                          size_t S, float noise_scale, uint64_t seed, uint32_t layer,
+                                                          float* __restrict__ out, int accumulate) {
   const size_t g4 = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t e = g4 * 4;
   if (e >= S) return;
@@ -200,13 +203,15 @@ __global__ __launch_bounds__(256) void explicit_sum_noise_kernel(const float* __
   }
   for (int i = 0; i < B; ++i) {
     const float* g = G + (size_t)i * S + e;
+    const float c = factors ? factors[i] : 1.0f;
     if (vec) {
-      const float4 v = *(const float4*)g;
-      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      const f32x4_t v = __builtin_nontemporal_load((const f32x4_t*)g);
+      acc[0] = fmaf(c, v.x, acc[0]); acc[1] = fmaf(c, v.y, acc[1]); acc[2] = fmaf(c, v.z, acc[2]); acc[3] = fmaf(c, v.w, acc[3]);
     } else {
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        if (e + q < S) acc[q] += g[q];
+        if (e + q < S) acc[q] = fmaf(c, g[q], acc[q]);
     }
   }
   if (noise_scale != 0.0f) {
@@ -214,9 +219,13 @@ __global__ __launch_bounds__(256) void explicit_sum_noise_kernel(const float* __
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[q] = fmaf(noise_scale, z.z[q], acc[q]);
   }
+  if (vec) {
+    *(float4*)(out + e) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  } else {
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
-    if (e + q < S) out[e + q] = acc[q];
+    for (int q = 0; q < 4; ++q)
+      if (e + q < S) out[e + q] = acc[q];
+  }
 }
 
 // out[e] = (ADD ? out[e] : 0) + scale * z[e]: the noise step alone (second pass of the two-pass schedule,

@@ -13,6 +13,7 @@
 
 #include "elementwise.hip.h"
 #include "gemm_mfma.hip.h"
+#include "gemm_mfma_f32.hip.h"
 #include "gemm_simple.hip.h"
 
 using namespace flashdp;
@@ -48,7 +49,7 @@ using Cfg256x8 = TileCfg<256, 256, 64, 2, 4>;   // 8 waves, 128x64 per wave
 using Cfg128x4 = TileCfg<128, 128, 64, 2, 2>;   // 4 waves, 64x64 per wave
 using Cfg256x8k32 = TileCfg<256, 256, 32, 2, 4>; // 8 waves, 32-deep k-tiles (half the LDS)
 
-enum Path { PATH_SIMPLE = 0, PATH_256x4 = 1, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4 };
+enum Path { PATH_SIMPLE = 0, PATH_256x4 = 1, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5 };
 
 struct Plan {
   Path path;         // per-sample passes (norm, spill)
@@ -66,11 +67,16 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
   Plan p;
   const bool mfma_ok = dtype != FLASHDP_F32 && P % 8 == 0 && D % 8 == 0 &&
                        (T + 192) * (P > D ? P : D) * 2 < (int64_t(1) << 31);   // incl. two parked prefetches past the end
-  if (!mfma_ok) {
+  // fp32 inputs: fp32 matrix-core kernel when rows are 16-byte multiples and the problem spans a few tiles
+  const bool f32_ok = dtype == FLASHDP_F32 && P % 4 == 0 && D % 4 == 0 && P * D >= 128 * 128 &&
+                      (T + 48) * (P > D ? P : D) * 4 < (int64_t(1) << 31) && env_int("FLASHDP_TILE", 0) != -1;
+  if (f32_ok) {
+    p.path = p.accum_path = PATH_F32; p.bm = p.bn = 256;
+  } else if (!mfma_ok) {
     p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
     int choice = env_int("FLASHDP_TILE", 0);
-    if (choice < 0 || choice > PATH_256x8k32) choice = 0;
+    if (choice < 0 || choice > PATH_256x8k32) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
     if (choice == 0) {
       // enough 256x256 work items to fill 256 CUs a few times over, else the smaller tile.
       // Measured on MI355X (Llama-13B up_proj, B = 8, norm pass): 8 waves of 128x64 with 32-deep k-tiles
@@ -141,6 +147,19 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& a, hipStream_t st) {
   }
   const int tiles = a.tiles_m * a.tiles_n;
   const int grid = (MODE == MODE_ACCUM) ? tiles : tiles * a.B;
+  if constexpr (DT == DT_F32) {
+    if (p.path == PATH_F32) {
+      static bool attr_set = false;
+      auto kern = gemm_mfma_f32_kernel<MODE>;
+      if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, F32Cfg::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+      }
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(F32Cfg::NT), F32Cfg::LDS_BYTES, st, a);
+      return hipGetLastError();
+    }
+  }
   hipLaunchKernelGGL((gemm_simple_kernel<MODE, DT>), dim3(grid), dim3(256), 0, st, a);
   return hipGetLastError();
 }
@@ -171,7 +190,7 @@ hipError_t launch_aggregate(int dtype, const void* scratch, const float* factors
     else if (dtype == FLASHDP_F16)
       hipLaunchKernelGGL((aggregate_generic_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
     else
-      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F32>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
+      hipLaunchKernelGGL(aggregate32_kernel, dim3(grid), dim3(256), 0, st, (const float*)scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
   }
   return hipGetLastError();
 }
@@ -280,8 +299,8 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mod
       HIP_TRY(hipGetLastError());
     }
     if (stages & FLASHDP_STAGE_AGGREGATE) {
-      hipLaunchKernelGGL(explicit_sum_noise_kernel, dim3((unsigned)(((S + 3) / 4 + 255) / 256)), dim3(256), 0, st, G, (int)B, S, noise_scale,
-                         L.seed, L.layer, L.out_grad, accumulate ? 1 : 0);                                                             // stage 4
+      hipLaunchKernelGGL(aggregate32_kernel, dim3((unsigned)(((S + 3) / 4 + 255) / 256)), dim3(256), 0, st, G, (const float*)nullptr, (int)B, S,
+                         noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0);                                                             // stage 4
       HIP_TRY(hipGetLastError());
     }
   } else if (use_scratch) {

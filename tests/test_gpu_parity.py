@@ -137,7 +137,7 @@ def test_odd_dims_take_generic_kernel(schedule):
 
 
 @pytest.mark.parametrize("schedule", ["twopass", "scratch", "explicit"])
-@pytest.mark.parametrize("shape", [(3, 100, 136, 264), (2, 33, 50, 70)])
+@pytest.mark.parametrize("shape", [(3, 100, 136, 264), (2, 33, 50, 70), (3, 70, 332, 520), (2, 16, 128, 128)])
 def test_f16_and_fp32_inputs(schedule, shape):
     B, T, P, D = shape
     rng = np.random.default_rng(B * T)
@@ -303,3 +303,24 @@ def test_gradient_accumulation_over_micro_batches(schedule, shape):
     # and it equals the one-call result on the whole batch up to fp32 summation order
     whole, _, _ = run_layer(X, dY, 1.0, 0.0, seed, layer, schedule)
     assert rel_fro(res[0.0], whole.astype(np.float64)) <= 1e-6
+
+
+def test_fp32_matrix_core_and_generic_kernels_agree():
+    # the same fp32 problem through the fp32 matrix-core kernel and (FLASHDP_TILE=-1) the generic kernel
+    rng = np.random.default_rng(12)
+    B, T, P, D = 3, 90, 260, 388
+    X = rng.standard_normal((B, T, P)).astype(np.float32)
+    dY = (rng.standard_normal((B, T, D)) * 0.02 * np.array([0.1, 1, 10], np.float32)[:, None, None]).astype(np.float32)
+    want, wn = O.linear_dp_grad(X, dY, 1.0, 0.0, 2, 0)
+    for schedule in ("scratch", "twopass"):
+        a = run_layer(X, dY, 1.0, 0.0, 2, 0, schedule)
+        b = run_layer(X, dY, 1.0, 0.0, 2, 0, schedule, tile=-1)
+        for got in (a, b):
+            assert rel_fro(got[0], want) <= 5e-5 and np.max(np.abs(got[1] - wn) / wn) <= 1e-4
+        assert rel_fro(a[0], b[0].astype(np.float64)) <= 1e-5
+    dX, ddY = to_device(X), to_device(dY)
+    plain = torch.full((D, P), float("nan"), device=DEV)
+    F.flashdp_plain_grad(dX, ddY, B, T, P, D, F.F32, plain)
+    torch.cuda.synchronize()
+    ref = dY.reshape(B * T, D).astype(np.float64).T @ X.reshape(B * T, P).astype(np.float64)
+    assert rel_fro(plain.cpu().numpy(), ref) <= 5e-6
