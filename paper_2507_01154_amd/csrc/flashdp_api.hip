@@ -44,12 +44,11 @@ inline size_t elt_bytes(int dtype) { return dtype == FLASHDP_F32 ? 4 : 2; }
 
 // ---- kernel plans --------------------------------------------------------------------------------
 
-using Cfg256x4 = TileCfg<256, 256, 64, 2, 2>;   // 4 waves, 128x128 per wave
 using Cfg256x8 = TileCfg<256, 256, 64, 2, 4>;   // 8 waves, 128x64 per wave
 using Cfg128x4 = TileCfg<128, 128, 64, 2, 2>;   // 4 waves, 64x64 per wave
 using Cfg256x8k32 = TileCfg<256, 256, 32, 2, 4>; // 8 waves, 32-deep k-tiles (half the LDS)
 
-enum Path { PATH_SIMPLE = 0, PATH_256x4 = 1, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5 };
+enum Path { PATH_SIMPLE = 0, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5 };
 
 struct Plan {
   Path path;         // per-sample passes (norm, spill)
@@ -66,7 +65,7 @@ int env_int(const char* name, int dflt) {
 Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
   Plan p;
   const bool mfma_ok = dtype != FLASHDP_F32 && P % 8 == 0 && D % 8 == 0 &&
-                       (T + 192) * (P > D ? P : D) * 2 < (int64_t(1) << 31);   // incl. two parked prefetches past the end
+                       (T + 320) * (P > D ? P : D) * 2 < (int64_t(1) << 31);   // incl. the parked prefetches past the end
   // fp32 inputs: fp32 matrix-core kernel when rows are 16-byte multiples and the problem spans a few tiles
   const bool f32_ok = dtype == FLASHDP_F32 && P % 4 == 0 && D % 4 == 0 && P * D >= 128 * 128 &&
                       (T + 48) * (P > D ? P : D) * 4 < (int64_t(1) << 31) && env_int("FLASHDP_TILE", 0) != -1;
@@ -76,12 +75,12 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
     int choice = env_int("FLASHDP_TILE", 0);
-    if (choice < 0 || choice > PATH_256x8k32) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
+    if (choice < PATH_256x8 || choice > PATH_256x8k32) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
     if (choice == 0) {
       // enough 256x256 work items to fill 256 CUs a few times over, else the smaller tile.
       // Measured on MI355X (Llama-13B up_proj, B = 8, norm pass): 8 waves of 128x64 with 32-deep k-tiles
-      // 1.16 PFLOP/s, with 64-deep k-tiles 1.05-1.10, 4 waves of 128x128 0.96 (one wave per SIMD hides
-      // less latency and spills).
+      // 1.16 PFLOP/s, with 64-deep k-tiles 1.05-1.10; 4 waves of 128x128 (one wave per SIMD) reached 0.96
+      // and spilled registers, and is no longer built.
       const int64_t items = ((D + 255) / 256) * ((P + 255) / 256) * B;
       choice = items >= 1024 ? PATH_256x8k32 : PATH_128x4;
     }
@@ -138,7 +137,6 @@ template <int MODE, int DT>
 hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& a, hipStream_t st) {
   if constexpr (DT != DT_F32) {
     switch (MODE == MODE_ACCUM ? p.accum_path : p.path) {
-      case PATH_256x4: return launch_mfma<Cfg256x4, MODE, DT>(a, st);
       case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
       case PATH_256x8k32: return launch_mfma<Cfg256x8k32, MODE, DT>(a, st);

@@ -273,8 +273,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
   load_frags(0, 0, fa[0], fb[0]);
 
   constexpr int N_MMA = FM * FN, N_RD = 2 * (FM + FN);
-  for (int k = 0; k < nk; ++k) {
-    const int cur = k & 1;
+  // One k-tile; `cur` is the LDS stage it computes from.
+  auto k_tile = [&](int k, int cur) {
     static_for<KS>([&](auto ks_c) {
       constexpr int ks = decltype(ks_c)::value;
       constexpr int cb = ks & 1, nb = cb ^ 1;
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
     if constexpr (MODE == MODE_ACCUM) {
       // sample boundary: rescale so that acc always holds sum_{j<=i} (c_j / c_i) G_j; exact up to one
       // fp32 rounding per boundary, and needs no second set of accumulators
-      if (a.factors != nullptr && (k + 1) % kt_per_sample == 0) {
+      if (a.factors != nullptr && k < nk && (k + 1) % kt_per_sample == 0) {
         const int s = k / kt_per_sample;
         const float ratio = (s + 1 < n_samples) ? a.factors[s] / a.factors[s + 1] : a.factors[s];
 #pragma unroll
@@ -308,6 +308,17 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
             for (int e = 0; e < 16; ++e) acc[i][j][e] *= ratio;
       }
     }
+  };
+  if constexpr (KS >= 4) {
+    // 64-deep k-tiles: two k-tiles per loop trip with the LDS stage a compile-time constant (measured 3 %
+    // faster); an odd tile count runs one extra k-tile on the zeros the parked fetch cursor delivers.
+    for (int k = 0; k < nk; k += 2) {
+      k_tile(k, 0);
+      k_tile(k + 1, 1);
+    }
+  } else {
+    // 32-deep k-tiles: the same unrolling measured 2 % slower, so one k-tile per trip
+    for (int k = 0; k < nk; ++k) k_tile(k, k & 1);
   }
   __syncthreads();   // the reduction below reuses the LDS tiles
 

@@ -118,7 +118,7 @@ SMALL = [
 
 @pytest.mark.parametrize("shape", SMALL)
 @pytest.mark.parametrize("schedule", ["twopass", "scratch", "explicit"])
-@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [2, 3, 4])
 def test_small_bf16_all_tiles(shape, schedule, tile):
     B, T, P, D = shape
     base = W.WORKLOADS["gpt2_small_mlp_up"]
@@ -178,7 +178,7 @@ def test_plain_grad_is_the_unclipped_limit():
     D = dY.shape[2]
     dX, ddY = to_device(X), to_device(dY)
     want = O.widen(dY).reshape(B * T, D).T @ O.widen(X).reshape(B * T, P)        # Eq. batched-grad
-    for tile in (1, 2, 3):
+    for tile in (2, 3, 4):
         out = torch.full((D, P), float("nan"), device=DEV)
         with env(FLASHDP_TILE=tile):
             F.flashdp_plain_grad(dX, ddY, B, T, P, D, F.BF16, out)
