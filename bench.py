@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama13b_block")
-    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch", "explicit"])
+    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch", "explicit", "overlap"])
     ap.add_argument("--no-schedule-comparison", action="store_true",
                     help="skip timing the other schedules (two-pass recompute, explicit four-stage) beside the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -128,8 +128,8 @@ def main():
     sched = args.schedule
     ws = None
     if sched != "twopass":
-        ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, "explicit" if sched == "explicit" else "scratch"),
-                         dtype=torch.uint8, device=dev)
+        ws_kind = {"explicit": "explicit", "scratch": "scratch"}.get(sched, "overlap")
+        ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, ws_kind), dtype=torch.uint8, device=dev)
 
     def step():
         F.flashdp_block_dp_grad(arr, w.B, w.T, dtype_code, sched, ws)
@@ -148,6 +148,7 @@ def main():
     step()
     torch.cuda.synchronize()
     hw_flops = flops * (2.0 if used == "twopass" else 1.0)
+    traffic_key = "scratch" if used == "overlap" else used
     n_launch = len(w.layers)
     roofline = {
         "bound": "mfma", "kernel": "gemm_mfma_kernel (per-sample contraction + norm)",
@@ -156,7 +157,7 @@ def main():
         "launches_per_step": n_launch, "avg_launch_ms": round(ms_contract / n_launch, 4),
         "flops_per_launch": flops / n_launch, "traffic": None,
     }
-    mt = MEASURED_TRAFFIC.get((w.name, used))
+    mt = MEASURED_TRAFFIC.get((w.name, traffic_key))
     if mt:
         roofline["traffic"] = mt["read_bytes"] + mt["write_bytes"]
         roofline["traffic_detail"] = dict(mt, algorithmic_read_bytes=sum(2.0 * w.B * w.T * (s.d_in + s.d_out) for s in w.layers) / n_launch,
@@ -199,7 +200,7 @@ def main():
         # the same step under the other schedules: two-pass recompute (the paper's "implicit" class) and the
         # explicit four-stage flow with materialised fp32 per-sample gradients (its "explicit" class)
         cmp = {used: round(ms, 4)}
-        for other in ("scratch", "twopass", "explicit"):
+        for other in ("overlap", "scratch", "twopass", "explicit"):
             if other in cmp:
                 continue
             ws_o = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, other), dtype=torch.uint8, device=dev)

@@ -71,8 +71,16 @@ enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
  *   EXPLICIT the explicit four-stage flow of Appendix B.2, one kernel per stage, the fp32 per-sample
  *            gradients written to and re-read from HBM between stages (workspace: 4 * B * d_out * d_in
  *            bytes).  Never chosen by AUTO: it exists to be measured against;
- *   AUTO     SCRATCH when the workspace is large enough, else TWOPASS.                                 */
-enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2, FLASHDP_SCHEDULE_EXPLICIT = 3 };
+ *   OVERLAP  SCRATCH for a block of two or more layers with the streaming kernel of layer l running on a
+ *            second, library-owned stream (default priority) beside the contraction of layer l+1
+ *            (workspace: two scratch slots).  Same arithmetic, bit-identical results.  The caller's
+ *            stream is made to wait for the side stream before the call's work counts as complete, so
+ *            stream-order semantics are unchanged.  Falls back to SCRATCH for a single layer, fp32 inputs
+ *            or small shapes;
+ *   AUTO     OVERLAP when it applies and the workspace holds two slots, else SCRATCH when it holds one,
+ *            else TWOPASS.                                                                              */
+enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2, FLASHDP_SCHEDULE_EXPLICIT = 3,
+       FLASHDP_SCHEDULE_OVERLAP = 4 };
 
 /* One linear layer of a block (Appendix A.1, "Per-Layer Gradient Processing": every layer is clipped
  * by its own norm with its own C and sigma). */
@@ -150,10 +158,10 @@ int flashdp_set_schedule(int schedule);
 enum { FLASHDP_STAGE_CONTRACT = 1, FLASHDP_STAGE_CLIP = 2, FLASHDP_STAGE_AGGREGATE = 4, FLASHDP_STAGE_ALL = 7 };
 int flashdp_set_stages(int mask);
 
-/* Frees the library-owned workspaces (synchronises the device first). */
+/* Frees the library-owned workspaces, side streams and events (synchronises the device first). */
 int flashdp_release(void);
 
-/* Name of the schedule the last call on this thread used: "twopass", "scratch" or "explicit" ("none" before any). */
+/* Name of the schedule the last call on this thread used: "twopass", "scratch", "overlap" or "explicit" ("none" before any). */
 const char* flashdp_last_schedule(void);
 
 const char* flashdp_status_string(int status);

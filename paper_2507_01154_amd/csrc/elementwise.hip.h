@@ -67,6 +67,20 @@ __global__ __launch_bounds__(256) void aggregate16_kernel(const void* __restrict
   aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
 }
 
+// The same work with a fixed, small number of workgroups striding over the elements: the form that runs on
+// a second stream beside the next layer's contraction kernel.  The ordinary grid would take every slot a
+// finishing contraction workgroup frees and starve the contraction (its workgroups need a whole CU's LDS)
+// until the aggregation is done; a bounded grid becomes resident once and leaves the rest of the chip alone.
+template <int DT>
+__global__ __launch_bounds__(256) void aggregate16_persistent_kernel(const void* __restrict__ scratch,
+                                                                     const float* __restrict__ factors, int B, size_t S,
+                                                                     size_t n8, float noise_scale, uint64_t seed,
+                                                                     uint32_t layer, float* __restrict__ out, int accumulate) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += stride)
+    aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
+}
+
 template <int DT>
 __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch, const float* __restrict__ factors, int B,
                                                 size_t S, size_t v, float noise_scale, uint64_t seed, uint32_t layer,

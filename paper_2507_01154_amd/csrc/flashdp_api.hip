@@ -10,6 +10,7 @@
 #include <cstring>
 #include <map>
 #include <mutex>
+#include <vector>
 
 #include "elementwise.hip.h"
 #include "gemm_mfma.hip.h"
@@ -36,10 +37,17 @@ struct OwnedWs { void* ptr = nullptr; size_t bytes = 0; };
 std::mutex g_ws_mutex;
 std::map<int, OwnedWs> g_owned;   // device -> library-owned workspace
 
+// Per-device second stream and events of the overlapped schedule (default priority, created on first use).
+struct SideStream {
+  hipStream_t stream = nullptr;
+  std::vector<hipEvent_t> ready, done;   // per layer slot: clip factors ready / aggregation done
+};
+std::map<int, SideStream> g_side;
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == FLASHDP_BF16 || d == FLASHDP_F32 || d == FLASHDP_F16; }
-inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_EXPLICIT; }
+inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_OVERLAP; }
 inline size_t elt_bytes(int dtype) { return dtype == FLASHDP_F32 ? 4 : 2; }
 
 // ---- kernel plans --------------------------------------------------------------------------------
@@ -172,7 +180,15 @@ hipError_t launch_gemm(const Plan& p, int dtype, const GemmArgs& a, hipStream_t 
 }
 
 hipError_t launch_aggregate(int dtype, const void* scratch, const float* factors, int B, size_t S, float noise_scale,
-                            uint64_t seed, uint32_t layer, float* out, int accumulate, hipStream_t st) {
+                            uint64_t seed, uint32_t layer, float* out, int accumulate, hipStream_t st, int persistent_grid = 0) {
+  if (persistent_grid > 0 && dtype != FLASHDP_F32 && S % 8 == 0) {
+    const size_t n8 = S / 8;
+    if (dtype == FLASHDP_BF16)
+      hipLaunchKernelGGL((aggregate16_persistent_kernel<DT_BF16>), dim3(persistent_grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
+    else
+      hipLaunchKernelGGL((aggregate16_persistent_kernel<DT_F16>), dim3(persistent_grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
+    return hipGetLastError();
+  }
   if (dtype != FLASHDP_F32 && S % 8 == 0) {
     const size_t n8 = S / 8;
     const unsigned grid = (unsigned)((n8 + 255) / 256);
@@ -249,6 +265,7 @@ int resolve_schedule(int schedule) {
     if (!std::strcmp(s, "twopass")) return FLASHDP_SCHEDULE_TWOPASS;
     if (!std::strcmp(s, "scratch")) return FLASHDP_SCHEDULE_SCRATCH;
     if (!std::strcmp(s, "explicit")) return FLASHDP_SCHEDULE_EXPLICIT;
+    if (!std::strcmp(s, "overlap")) return FLASHDP_SCHEDULE_OVERLAP;
   }
   return schedule;
 }
@@ -261,10 +278,12 @@ size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype,
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; } } while (0)
 
 // Enqueues Algorithm 1 for one layer.
+// `parts` restricts what is enqueued (a subset of the stage mask); persistent_grid > 0 selects the bounded
+// aggregation grid of the overlapped schedule.
 int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mode, char* ws, hipStream_t st,
-              bool accumulate, bool add_noise) {
+              bool accumulate, bool add_noise, int parts = FLASHDP_STAGE_ALL, int persistent_grid = 0) {
   const bool use_scratch = mode == FLASHDP_SCHEDULE_SCRATCH;
-  const int stages = g_ctx.stages;
+  const int stages = g_ctx.stages & parts;
   const int64_t P = L.d_in, D = L.d_out;
   const Plan plan = make_plan(B, T, P, D, dtype);
   const WsLayout wl = ws_layout(plan, B, P, D, dtype, mode);
@@ -308,7 +327,7 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mod
       HIP_TRY(hipGetLastError());
     }
     if (stages & FLASHDP_STAGE_AGGREGATE)
-      HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0, st));
+      HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0, st, persistent_grid));
   } else {
     if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
     if (stages & FLASHDP_STAGE_CLIP) {
@@ -348,26 +367,78 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
   int dev = 0;
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
+  // The overlapped schedule needs two layers or more, 16-bit inputs on the large-tile matrix-core path
+  // (where the aggregation is worth hiding) and the full stage mask; otherwise it is the scratch schedule.
+  bool overlap_ok = n_layers >= 2 && dtype != FLASHDP_F32 && g_ctx.stages == FLASHDP_STAGE_ALL;
+  for (int l = 0; l < n_layers && overlap_ok; ++l) {
+    const Plan p = make_plan(B, T, layers[l].d_in, layers[l].d_out, dtype);
+    overlap_ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
+  }
+  const size_t slot = align_up(need_scratch, 256);
+  const size_t need_overlap = 2 * slot;
   char* ws = static_cast<char*>(workspace);
   int mode;
   if (workspace) {
     if (schedule == FLASHDP_SCHEDULE_AUTO) {
-      mode = workspace_bytes >= need_scratch ? FLASHDP_SCHEDULE_SCRATCH : FLASHDP_SCHEDULE_TWOPASS;
+      mode = (overlap_ok && workspace_bytes >= need_overlap) ? FLASHDP_SCHEDULE_OVERLAP
+             : workspace_bytes >= need_scratch ? FLASHDP_SCHEDULE_SCRATCH : FLASHDP_SCHEDULE_TWOPASS;
     } else {
       mode = schedule;
     }
-    const size_t need = mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
+    if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
+    const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
+                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
     if (workspace_bytes < need) return FLASHDP_WORKSPACE_TOO_SMALL;
   } else {
-    mode = schedule == FLASHDP_SCHEDULE_AUTO ? FLASHDP_SCHEDULE_SCRATCH : schedule;
-    const size_t need = mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
+    mode = schedule == FLASHDP_SCHEDULE_AUTO ? (overlap_ok ? FLASHDP_SCHEDULE_OVERLAP : FLASHDP_SCHEDULE_SCRATCH) : schedule;
+    if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
+    const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
+                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
     void* p = nullptr; size_t got = 0;
     st = owned_workspace(need, &p, &got);
     if (st != FLASHDP_OK) return st;
     ws = static_cast<char*>(p);
   }
+  hipStream_t main_st = static_cast<hipStream_t>(stream);
+  if (mode == FLASHDP_SCHEDULE_OVERLAP) {
+    // Layer l: contraction + clip factors on the caller's stream into scratch slot l % 2; its aggregation
+    // on the side stream, beside the contraction of layer l+1.  Events order the two streams; the caller's
+    // stream waits for the last aggregations before the call's work counts as complete.
+    SideStream* side = nullptr;
+    {
+      std::lock_guard<std::mutex> lock(g_ws_mutex);
+      side = &g_side[dev];
+      if (!side->stream) HIP_TRY(hipStreamCreateWithFlags(&side->stream, hipStreamNonBlocking));
+      while ((int)side->ready.size() < n_layers) {
+        hipEvent_t e1 = nullptr, e2 = nullptr;
+        HIP_TRY(hipEventCreateWithFlags(&e1, hipEventDisableTiming));
+        HIP_TRY(hipEventCreateWithFlags(&e2, hipEventDisableTiming));
+        side->ready.push_back(e1);
+        side->done.push_back(e2);
+      }
+    }
+    const int grid = env_int("FLASHDP_OVERLAP_GRID", 512);
+    for (int l = 0; l < n_layers; ++l) {
+      char* wsl = ws + (size_t)(l & 1) * slot;
+      if (l >= 2) HIP_TRY(hipStreamWaitEvent(main_st, side->done[l - 2], 0));   // slot free again
+      st = run_layer(layers[l], B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, main_st, accumulate != 0, add_noise != 0,
+                     FLASHDP_STAGE_CONTRACT | FLASHDP_STAGE_CLIP);
+      if (st != FLASHDP_OK) return st;
+      HIP_TRY(hipEventRecord(side->ready[l], main_st));
+      HIP_TRY(hipStreamWaitEvent(side->stream, side->ready[l], 0));
+      // the last layer has nothing to hide behind: ordinary grid
+      st = run_layer(layers[l], B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, side->stream, accumulate != 0, add_noise != 0,
+                     FLASHDP_STAGE_AGGREGATE, l + 1 < n_layers ? grid : 0);
+      if (st != FLASHDP_OK) return st;
+      HIP_TRY(hipEventRecord(side->done[l], side->stream));
+    }
+    HIP_TRY(hipStreamWaitEvent(main_st, side->done[n_layers - 1], 0));
+    HIP_TRY(hipStreamWaitEvent(main_st, side->done[n_layers - 2], 0));
+    g_ctx.last_schedule = "overlap";
+    return FLASHDP_OK;
+  }
   for (int l = 0; l < n_layers; ++l) {
-    st = run_layer(layers[l], B, T, dtype, mode, ws, static_cast<hipStream_t>(stream), accumulate != 0, add_noise != 0);
+    st = run_layer(layers[l], B, T, dtype, mode, ws, main_st, accumulate != 0, add_noise != 0);
     if (st != FLASHDP_OK) return st;
   }
   g_ctx.last_schedule = mode == FLASHDP_SCHEDULE_SCRATCH ? "scratch" : mode == FLASHDP_SCHEDULE_EXPLICIT ? "explicit" : "twopass";
@@ -392,8 +463,10 @@ size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int6
   size_t need = 0;
   for (int l = 0; l < n_layers; ++l) {
     if (check_dims(B, T, layers[l].d_in, layers[l].d_out) != FLASHDP_OK) return 0;
-    need = std::max(need, layer_ws_bytes(layers[l], B, T, dtype, schedule == FLASHDP_SCHEDULE_AUTO ? FLASHDP_SCHEDULE_SCRATCH : schedule));
+    const int m = (schedule == FLASHDP_SCHEDULE_AUTO || schedule == FLASHDP_SCHEDULE_OVERLAP) ? FLASHDP_SCHEDULE_SCRATCH : schedule;
+    need = std::max(need, layer_ws_bytes(layers[l], B, T, dtype, m));
   }
+  if (schedule == FLASHDP_SCHEDULE_OVERLAP) need = 2 * align_up(need, 256);
   return need;
 }
 
@@ -477,6 +550,14 @@ int flashdp_release(void) {
     (void)hipDeviceSynchronize();
     (void)hipFree(kv.second.ptr);
     kv.second = OwnedWs();
+  }
+  for (auto& kv : g_side) {
+    if (hipSetDevice(kv.first) != hipSuccess) continue;
+    (void)hipDeviceSynchronize();
+    for (hipEvent_t e : kv.second.ready) (void)hipEventDestroy(e);
+    for (hipEvent_t e : kv.second.done) (void)hipEventDestroy(e);
+    if (kv.second.stream) (void)hipStreamDestroy(kv.second.stream);
+    kv.second = SideStream();
   }
   if (have_cur) (void)hipSetDevice(cur);
   (void)hipGetLastError();

@@ -124,3 +124,43 @@ def run_workload_sched(w, sigma, schedule):
     torch.cuda.synchronize()
     outs = [(L["out_grad"].cpu().numpy(), L["out_norms"].cpu().numpy()) for L in layers]
     return host, outs, F.flashdp_last_schedule()
+
+
+@pytest.mark.timeout(600)
+def test_overlapped_schedule_is_bit_identical_to_scratch(block_runs):
+    """The overlapped schedule reorders kernels across two streams, nothing else: same bits as the scratch
+    schedule, on repeated calls (events and scratch slots are reused), and noise included."""
+    w, host, o0, o1, used = block_runs
+    layers = []
+    for l, spec in enumerate(w.layers):
+        X, dY = host[l]
+        out = torch.full((spec.d_out, spec.d_in), float("nan"), device=DEV)
+        norms = torch.full((w.B,), float("nan"), device=DEV)
+        layers.append(dict(X=to_device(X), dY=to_device(dY), d_in=spec.d_in, d_out=spec.d_out, C=w.C, sigma=w.sigma,
+                           seed=w.layer_seed(l), layer=l, out_grad=out, out_norms=norms))
+    arr = F.make_layers(layers)
+    need = F.flashdp_workspace_bytes(arr, w.B, w.T, F.BF16, "overlap")
+    assert need >= 2 * F.flashdp_workspace_bytes(arr, w.B, w.T, F.BF16, "scratch") - 512
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    for rep in range(3):
+        for L in layers:
+            L["out_grad"].fill_(float("nan"))
+        F.flashdp_block_dp_grad(arr, w.B, w.T, F.BF16, "auto" if rep == 2 else "overlap", ws)
+        torch.cuda.synchronize()
+        assert F.flashdp_last_schedule() == "overlap"
+        for l, L in enumerate(layers):
+            assert np.array_equal(L["out_grad"].cpu().numpy(), o1[l][0]), (rep, l)
+            assert np.array_equal(L["out_norms"].cpu().numpy(), o1[l][1]), (rep, l)
+    # a workspace with one slot only: auto stays on the scratch schedule; an explicit request is refused
+    F.flashdp_block_dp_grad(arr, w.B, w.T, F.BF16, "auto", ws[: need // 2])
+    torch.cuda.synchronize()
+    assert F.flashdp_last_schedule() == "scratch"
+    with pytest.raises(F.FlashDPError) as ei:
+        F.flashdp_block_dp_grad(arr, w.B, w.T, F.BF16, "overlap", ws[: need // 2])
+    assert ei.value.status == F.WORKSPACE_TOO_SMALL
+    # a single layer has nothing to overlap with
+    one = F.make_layers(layers[:1])
+    F.flashdp_block_dp_grad(one, w.B, w.T, F.BF16, "overlap", ws)
+    torch.cuda.synchronize()
+    assert F.flashdp_last_schedule() == "scratch"
+    assert np.array_equal(layers[0]["out_grad"].cpu().numpy(), o1[0][0])
