@@ -66,7 +66,8 @@ enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
  *   TWOPASS  norm pass, then a second contraction that accumulates c_i G_i (each G_i computed twice;
  *            workspace: a few KB);
  *   SCRATCH  each G_i tile is computed once, its square-sum taken from the fp32 accumulators, the tile
- *            parked in a per-layer scratch (16-bit for 16-bit inputs, fp32 for fp32 inputs), and a
+ *            parked in a per-layer scratch (bfloat16 for both 16-bit input types - fp16's range could
+ *            overflow on an unclipped gradient -, fp32 for fp32 inputs), and a
  *            streaming kernel forms sum_i c_i G_i + noise (workspace: B * d_out * d_in elements);
  *   EXPLICIT the explicit four-stage flow of Appendix B.2, one kernel per stage, the fp32 per-sample
  *            gradients written to and re-read from HBM between stages (workspace: 4 * B * d_out * d_in

@@ -183,26 +183,18 @@ hipError_t launch_aggregate(int dtype, const void* scratch, const float* factors
                             uint64_t seed, uint32_t layer, float* out, int accumulate, hipStream_t st, int persistent_grid = 0) {
   if (persistent_grid > 0 && dtype != FLASHDP_F32 && S % 8 == 0) {
     const size_t n8 = S / 8;
-    if (dtype == FLASHDP_BF16)
-      hipLaunchKernelGGL((aggregate16_persistent_kernel<DT_BF16>), dim3(persistent_grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
-    else
-      hipLaunchKernelGGL((aggregate16_persistent_kernel<DT_F16>), dim3(persistent_grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
+    hipLaunchKernelGGL((aggregate16_persistent_kernel<DT_BF16>), dim3(persistent_grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
     return hipGetLastError();
   }
   if (dtype != FLASHDP_F32 && S % 8 == 0) {
     const size_t n8 = S / 8;
     const unsigned grid = (unsigned)((n8 + 255) / 256);
-    if (dtype == FLASHDP_BF16)
-      hipLaunchKernelGGL((aggregate16_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
-    else
-      hipLaunchKernelGGL((aggregate16_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
+    hipLaunchKernelGGL((aggregate16_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, n8, noise_scale, seed, layer, out, accumulate);
   } else {
     const size_t groups = (S + 3) / 4;
     const unsigned grid = (unsigned)((groups + 255) / 256);
-    if (dtype == FLASHDP_BF16)
+    if (dtype != FLASHDP_F32)   // the scratch of both 16-bit input types is bfloat16
       hipLaunchKernelGGL((aggregate_generic_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
-    else if (dtype == FLASHDP_F16)
-      hipLaunchKernelGGL((aggregate_generic_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
     else
       hipLaunchKernelGGL(aggregate32_kernel, dim3(grid), dim3(256), 0, st, (const float*)scratch, factors, B, S, noise_scale, seed, layer, out, accumulate);
   }

@@ -74,7 +74,7 @@ struct GemmArgs {
   int B, T, P, D;
   int tiles_m, tiles_n;  // ceil(D / BM), ceil(P / BN)
   float* partials;       // [B][tiles_m * tiles_n] squared-norm partial sums (NORM, SPILL)
-  void* scratch;         // [B][D][P] 16-bit (SPILL) or fp32 (MATERIALIZE)
+  void* scratch;         // [B][D][P] bfloat16 (SPILL, also for fp16 inputs), fp32 (SPILL of fp32 inputs, MATERIALIZE)
   const float* factors;  // [B] clip factors (ACCUM); nullptr = all ones
   float* out;            // [D][P] (ACCUM)
   int accumulate;        // ACCUM: add to what out holds (gradient accumulation over micro-batches) instead of overwriting
@@ -353,8 +353,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             uint2 v;
-            v.x = pack2_16bit<DT>(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
-            v.y = pack2_16bit<DT>(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            // the scratch is bfloat16 for fp16 inputs too: a per-sample gradient before clipping has no
+            // bound, and fp16's range (65504) would turn a large one into inf
+            v.x = pack2_16bit<DT_BF16>(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+            v.y = pack2_16bit<DT_BF16>(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
             *(uint2*)(st + (i * 32) * EP + j * 32 + 8 * q) = v;
           }
     }

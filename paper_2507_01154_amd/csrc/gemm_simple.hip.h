@@ -25,7 +25,7 @@ __device__ __forceinline__ void store_scratch(void* p, size_t idx, float v) {
   if constexpr (DT == DT_F32) {
     ((float*)p)[idx] = v;
   } else {
-    ((unsigned short*)p)[idx] = to_16bit<DT>(v);
+    ((unsigned short*)p)[idx] = to_16bit<DT_BF16>(v);   // bfloat16 scratch for both 16-bit input types (range)
   }
 }
 
