@@ -43,6 +43,7 @@ struct SideStream {
   std::vector<hipEvent_t> ready, done;   // per layer slot: clip factors ready / aggregation done
 };
 std::map<int, SideStream> g_side;
+std::mutex g_side_mutex;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -396,18 +397,18 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     // Layer l: contraction + clip factors on the caller's stream into scratch slot l % 2; its aggregation
     // on the side stream, beside the contraction of layer l+1.  Events order the two streams; the caller's
     // stream waits for the last aggregations before the call's work counts as complete.
-    SideStream* side = nullptr;
-    {
-      std::lock_guard<std::mutex> lock(g_ws_mutex);
-      side = &g_side[dev];
-      if (!side->stream) HIP_TRY(hipStreamCreateWithFlags(&side->stream, hipStreamNonBlocking));
-      while ((int)side->ready.size() < n_layers) {
-        hipEvent_t e1 = nullptr, e2 = nullptr;
-        HIP_TRY(hipEventCreateWithFlags(&e1, hipEventDisableTiming));
-        HIP_TRY(hipEventCreateWithFlags(&e2, hipEventDisableTiming));
-        side->ready.push_back(e1);
-        side->done.push_back(e2);
-      }
+    // The side stream and its events are shared by every thread using this device: the whole enqueue
+    // sequence below is done under the lock, so that one call's record/wait pairs are never interleaved
+    // with another's (an event wait refers to the latest record at the time of the wait).
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStream* side = &g_side[dev];
+    if (!side->stream) HIP_TRY(hipStreamCreateWithFlags(&side->stream, hipStreamNonBlocking));
+    while ((int)side->ready.size() < n_layers) {
+      hipEvent_t e1 = nullptr, e2 = nullptr;
+      HIP_TRY(hipEventCreateWithFlags(&e1, hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&e2, hipEventDisableTiming));
+      side->ready.push_back(e1);
+      side->done.push_back(e2);
     }
     const int grid = env_int("FLASHDP_OVERLAP_GRID", 512);
     for (int l = 0; l < n_layers; ++l) {
@@ -543,6 +544,7 @@ int flashdp_release(void) {
     (void)hipFree(kv.second.ptr);
     kv.second = OwnedWs();
   }
+  std::lock_guard<std::mutex> side_lock(g_side_mutex);
   for (auto& kv : g_side) {
     if (hipSetDevice(kv.first) != hipSuccess) continue;
     (void)hipDeviceSynchronize();
