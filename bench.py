@@ -75,9 +75,9 @@ def time_events(fn, steps, warmup):
     return s.elapsed_time(e) / steps
 
 
-def cpu_baseline(w):
-    """The oracle as it stands on the host cores, on a bounded sample of the same workload: the largest
-    layer of the workload, full T, as many samples as keep the work near 10-30 s."""
+def cpu_baseline(w, target_flop=6e12):
+    """The oracle as it stands on the host cores, on a bounded sample of the same workload: whole layers
+    (all samples, full T), largest first, until about target_flop of work (10-30 s) has been timed."""
     import numpy as np
     import workloads as W
     from oracle import flashdp_oracle as O
@@ -86,18 +86,21 @@ def cpu_baseline(w):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    l = max(range(len(w.layers)), key=lambda k: w.layers[k].d_in * w.layers[k].d_out)
-    spec = w.layers[l]
-    per_sample = 2.0 * w.T * spec.d_in * spec.d_out
-    n = int(max(1, min(w.B, round(2.4e12 / per_sample))))
-    Xs, dYs = zip(*[W.make_sample(w, l, i) for i in range(n)])
-    X, dY = np.stack(Xs), np.stack(dYs)
-    t0 = time.perf_counter()
-    O.linear_dp_grad(X, dY, w.C, w.sigma, w.layer_seed(l), l)
-    dt = time.perf_counter() - t0
-    return {"value": round(n * per_sample / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+    order = sorted(range(len(w.layers)), key=lambda k: -w.layers[k].d_in * w.layers[k].d_out)
+    done_flop, dt, names = 0.0, 0.0, []
+    for l in order:
+        spec = w.layers[l]
+        X, dY = W.make_layer(w, l)
+        t0 = time.perf_counter()
+        O.linear_dp_grad(X, dY, w.C, w.sigma, w.layer_seed(l), l)
+        dt += time.perf_counter() - t0
+        done_flop += 2.0 * w.B * w.T * spec.d_in * spec.d_out
+        names.append(spec.name)
+        if done_flop >= target_flop:
+            break
+    return {"value": round(done_flop / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
             "seconds": round(dt, 2),
-            "sample": f"layer {spec.name} ({spec.d_in}->{spec.d_out}), {n} of {w.B} samples, T={w.T}, fp64 numpy oracle incl. noise field"}
+            "sample": f"layers {'+'.join(names)} of {w.name} (all {w.B} samples, T={w.T}), fp64 numpy oracle incl. noise field"}
 
 
 def main():
