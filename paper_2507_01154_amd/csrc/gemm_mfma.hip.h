@@ -19,7 +19,8 @@
 // The X fragment is passed as the first (row) operand and the dY fragment as the second, i.e. the
 // instruction forms the transposed block: lane l then owns output row m = l % 32 and, in registers
 // 4q..4q+3, four CONSECUTIVE output columns n = 8q + 4 * (l / 32) + 0..3, which the epilogue packs into one
-// 8-byte (16-bit scratch) or 16-byte (fp32) store instead of four scattered ones.
+// 8-byte LDS write (the bfloat16 tile is staged in LDS and leaves the chip in whole 512-byte rows: partial
+// cache lines from direct stores measured slower) or one 16-byte global store (fp32 output).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
