@@ -49,6 +49,12 @@ def parse():
 def time_steps(fn, steps, warmup):
     """Wall-clock over exactly `steps` calls, bracketed by device synchronisation; ms per step."""
     import torch
+    # untimed: bring the clocks up first (a sub-millisecond step would otherwise be timed on a GPU that is
+    # still ramping), then the W warm-up steps proper
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < 0.05:
+        fn()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
