@@ -38,6 +38,12 @@
  *     take a slower generic kernel.
  *   - NaN/Inf in the inputs propagate to out_norms / out_grad.
  *   - Return value: FLASHDP_OK (0) or a negative flashdp_status; on error nothing is enqueued.
+ *
+ * Environment overrides, read at every call (measurement aids, not needed in normal use):
+ *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit   replaces the schedule argument;
+ *   FLASHDP_TILE = 2 | 3 | 4     forces the matrix-core tile (256x256 with 64-deep k-tiles, 128x128,
+ *                                256x256 with 32-deep k-tiles); -1 sends fp32 inputs to the generic kernel;
+ *   FLASHDP_OVERLAP_GRID = n     workgroups of the aggregation kernel in the overlapped schedule (512).
  */
 #ifndef FLASHDP_H
 #define FLASHDP_H

@@ -89,3 +89,10 @@ def test_workspace_bytes_formula():
 def test_no_device_is_an_error_not_a_crash():
     assert F.lib().flashdp_linear_dp_grad(A, B_, 1, 1, 8, 8, 1.0, 0.0, 0, O_, None) == F.NO_DEVICE
     assert F.lib().flashdp_noise_field(1, 0, 16, O_, None) == F.NO_DEVICE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
