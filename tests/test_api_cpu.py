@@ -96,3 +96,14 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    import subprocess
+    exe = str(tmp_path / "abi_check")
+    lib_dir = os.path.join(ROOT, "paper_2507_01154_amd")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-o", exe, os.path.join(ROOT, "tests", "abi_check.c"),
+                           "-L" + lib_dir, "-lflashdp", "-Wl,-rpath," + lib_dir])
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.split()[0] == str(F.flashdp_version())

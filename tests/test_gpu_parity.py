@@ -338,3 +338,15 @@ def test_fp16_inputs_with_large_gradients_do_not_overflow_the_scratch():
         got, gn, _ = run_layer(X, dY, 1.0, 0.0, 0, 0, schedule)
         assert np.all(np.isfinite(got)) and rel_fro(got, want) <= 4e-3
         assert np.max(np.abs(gn - wn) / wn) <= 1e-4
+
+
+@pytest.mark.parametrize("schedule", ["scratch", "twopass"])
+def test_twenty_runs_are_bit_identical(schedule):
+    # every reduction has a fixed order (no atomics), so run-to-run differences would mean a race
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=5, T=200, dims=[(520, 776)])
+    X, dY = W.make_layer(w, 0)
+    first = run_layer(X, dY, 1.0, 1.0, 3, 2, schedule)
+    for _ in range(19):
+        again = run_layer(X, dY, 1.0, 1.0, 3, 2, schedule)
+        assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
