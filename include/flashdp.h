@@ -28,7 +28,9 @@
  *   - All data pointers are DEVICE pointers (HIP, current device) owned by the caller.
  *     flashdp_layer_t arrays and scalar arguments are HOST memory.
  *   - Calls enqueue work on a HIP stream and return without synchronising it.  Device
- *     faults surface at the caller's next synchronisation.
+ *     faults surface at the caller's next synchronisation.  With a caller-owned workspace a call
+ *     only launches kernels (plus event records/waits between its two streams in the overlapped
+ *     schedule), so it can be captured into a HIP graph once each kernel has been launched eagerly.
  *   - out_grad and out_norms are overwritten, never accumulated into.
  *   - Inputs are read-only.  X pointers of different layers may alias.
  *   - dtype: FLASHDP_BF16 / FLASHDP_F16 / FLASHDP_F32 is the storage type of X and dY; products are
