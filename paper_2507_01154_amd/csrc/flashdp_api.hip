@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -411,16 +412,24 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
       side->done.push_back(e2);
     }
     const int grid = env_int("FLASHDP_OVERLAP_GRID", 512);
+    // Layers are independent, so they are taken largest first: the one aggregation that has nothing to hide
+    // behind (the last) is then the smallest.
+    std::vector<int> order(n_layers);
+    for (int l = 0; l < n_layers; ++l) order[l] = l;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+      return layers[x].d_in * layers[x].d_out > layers[y].d_in * layers[y].d_out;
+    });
     for (int l = 0; l < n_layers; ++l) {
+      const flashdp_layer_t& Lr = layers[order[l]];
       char* wsl = ws + (size_t)(l & 1) * slot;
       if (l >= 2) HIP_TRY(hipStreamWaitEvent(main_st, side->done[l - 2], 0));   // slot free again
-      st = run_layer(layers[l], B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, main_st, accumulate != 0, add_noise != 0,
+      st = run_layer(Lr, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, main_st, accumulate != 0, add_noise != 0,
                      FLASHDP_STAGE_CONTRACT | FLASHDP_STAGE_CLIP);
       if (st != FLASHDP_OK) return st;
       HIP_TRY(hipEventRecord(side->ready[l], main_st));
       HIP_TRY(hipStreamWaitEvent(side->stream, side->ready[l], 0));
       // the last layer has nothing to hide behind: ordinary grid
-      st = run_layer(layers[l], B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, side->stream, accumulate != 0, add_noise != 0,
+      st = run_layer(Lr, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, side->stream, accumulate != 0, add_noise != 0,
                      FLASHDP_STAGE_AGGREGATE, l + 1 < n_layers ? grid : 0);
       if (st != FLASHDP_OK) return st;
       HIP_TRY(hipEventRecord(side->done[l], side->stream));
