@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama13b_block")
-    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch", "explicit", "overlap"])
+    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch", "explicit", "overlap", "ghost"])
     ap.add_argument("--no-schedule-comparison", action="store_true",
                     help="skip timing the other schedules (two-pass recompute, explicit four-stage) beside the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -137,7 +137,7 @@ def main():
     sched = args.schedule
     ws = None
     if sched != "twopass":
-        ws_kind = {"explicit": "explicit", "scratch": "scratch"}.get(sched, "overlap")
+        ws_kind = {"explicit": "explicit", "scratch": "scratch", "ghost": "ghost"}.get(sched, "overlap")
         ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, ws_kind), dtype=torch.uint8, device=dev)
 
     def step():
@@ -157,6 +157,8 @@ def main():
     step()
     torch.cuda.synchronize()
     hw_flops = flops * (2.0 if used == "twopass" else 1.0)
+    if used == "ghost":   # upper-triangular blocks of both T x T Gram matrices, then the gradient itself
+        hw_flops = flops + sum(float(w.B) * w.T * (w.T + 128) * (s.d_in + s.d_out) for s in w.layers)
     traffic_key = "scratch" if used == "overlap" else used
     n_launch = len(w.layers)
     roofline = {
@@ -207,9 +209,10 @@ def main():
 
     if not args.no_schedule_comparison:
         # the same step under the other schedules: two-pass recompute (the paper's "implicit" class) and the
-        # explicit four-stage flow with materialised fp32 per-sample gradients (its "explicit" class)
+        # explicit four-stage flow with materialised fp32 per-sample gradients (its "explicit" class), and the
+        # ghost-norm route (norms from T x T Gram matrices, then one clipped accumulation)
         cmp = {used: round(ms, 4)}
-        for other in ("overlap", "scratch", "twopass", "explicit"):
+        for other in ("overlap", "scratch", "twopass", "explicit", "ghost"):
             if other in cmp:
                 continue
             ws_o = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, other), dtype=torch.uint8, device=dev)

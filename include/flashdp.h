@@ -42,7 +42,7 @@
  *   - Return value: FLASHDP_OK (0) or a negative flashdp_status; on error nothing is enqueued.
  *
  * Environment overrides, read at every call (measurement aids, not needed in normal use):
- *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit   replaces the schedule argument;
+ *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit | ghost   replaces the schedule argument;
  *   FLASHDP_TILE = 2 | 3 | 4     forces the matrix-core tile (256x256 with 64-deep k-tiles, 128x128,
  *                                256x256 with 32-deep k-tiles); -1 sends fp32 inputs to the generic kernel;
  *   FLASHDP_OVERLAP_GRID = n     workgroups of the aggregation kernel in the overlapped schedule (512).
@@ -86,10 +86,15 @@ enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
  *            stream is made to wait for the side stream before the call's work counts as complete, so
  *            stream-order semantics are unchanged.  Falls back to SCRATCH for a single layer, fp32 inputs
  *            or small shapes;
+ *   GHOST    the norms come from the ghost-clipping identity the paper cites among the implicit methods
+ *            (Section 2): n_i^2 = <X_i X_i^T, dY_i dY_i^T>_F, two T x T Gram matrices per sample that are
+ *            never stored, then the clipped accumulation of TWOPASS (workspace: a few KB to MB of partial
+ *            sums).  Costs T^2 (d_in + d_out) extra FLOPs per sample instead of a second 2 T d_in d_out.
+ *            Never chosen by AUTO: it exists to be measured against;
  *   AUTO     OVERLAP when it applies and the workspace holds two slots, else SCRATCH when it holds one,
  *            else TWOPASS.                                                                              */
 enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2, FLASHDP_SCHEDULE_EXPLICIT = 3,
-       FLASHDP_SCHEDULE_OVERLAP = 4 };
+       FLASHDP_SCHEDULE_OVERLAP = 4, FLASHDP_SCHEDULE_GHOST = 5 };
 
 /* One linear layer of a block (Appendix A.1, "Per-Layer Gradient Processing": every layer is clipped
  * by its own norm with its own C and sigma). */

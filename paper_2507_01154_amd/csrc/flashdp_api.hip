@@ -17,6 +17,7 @@
 #include "gemm_mfma.hip.h"
 #include "gemm_mfma_f32.hip.h"
 #include "gemm_simple.hip.h"
+#include "gram_norm.hip.h"
 
 using namespace flashdp;
 
@@ -49,7 +50,7 @@ std::mutex g_side_mutex;
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == FLASHDP_BF16 || d == FLASHDP_F32 || d == FLASHDP_F16; }
-inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_OVERLAP; }
+inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_GHOST; }
 inline size_t elt_bytes(int dtype) { return dtype == FLASHDP_F32 ? 4 : 2; }
 
 // ---- kernel plans --------------------------------------------------------------------------------
@@ -113,13 +114,26 @@ int explicit_chunks(int64_t P, int64_t D) {
   return (int)(c < 1 ? 1 : (c > 2048 ? 2048 : c));
 }
 
-// mode: FLASHDP_SCHEDULE_TWOPASS (no scratch), _SCRATCH (input-width scratch), _EXPLICIT (fp32 scratch)
-WsLayout ws_layout(const Plan& p, int64_t B, int64_t P, int64_t D, int dtype, int mode) {
+// Ghost-norm schedule: matrix-core Gram kernel (128-row blocks) or the generic one (64-row blocks).
+bool gram_mfma_ok(int64_t T, int64_t P, int64_t D, int dtype) {
+  return dtype != FLASHDP_F32 && P % 8 == 0 && D % 8 == 0 && (T + 128) * (P > D ? P : D) * 2 < (int64_t(1) << 31);
+}
+int64_t gram_blocks(int64_t T, int64_t P, int64_t D, int dtype) {
+  const int64_t bt = gram_mfma_ok(T, P, D, dtype) ? GramCfg::BT : 64;
+  return (T + bt - 1) / bt;
+}
+
+// mode: FLASHDP_SCHEDULE_TWOPASS / _GHOST (no scratch), _SCRATCH (input-width scratch), _EXPLICIT (fp32 scratch)
+WsLayout ws_layout(const Plan& p, int64_t B, int64_t T, int64_t P, int64_t D, int dtype, int mode) {
   WsLayout w;
   w.factors = 0;
   w.partials = align_up((size_t)B * 4, 256);
   size_t n_part = (size_t)p.tiles_m * p.tiles_n;
   if (mode == FLASHDP_SCHEDULE_EXPLICIT) n_part = std::max(n_part, (size_t)explicit_chunks(P, D));
+  if (mode == FLASHDP_SCHEDULE_GHOST) {
+    const size_t nb = (size_t)gram_blocks(T, P, D, dtype);
+    n_part = std::max(n_part, nb * (nb + 1) / 2);
+  }
   w.scratch = w.partials + align_up((size_t)B * n_part * 4, 256);
   size_t sc = 0;
   if (mode == FLASHDP_SCHEDULE_SCRATCH) sc = (size_t)B * D * P * elt_bytes(dtype);
@@ -203,6 +217,28 @@ hipError_t launch_aggregate(int dtype, const void* scratch, const float* factors
   return hipGetLastError();
 }
 
+hipError_t launch_gram(int dtype, bool mfma, const GramArgs& g, hipStream_t st) {
+  const unsigned grid = (unsigned)((int64_t)g.B * g.n_tri);
+  if (mfma) {
+    static bool attr_set[2] = {false, false};
+    const int which = dtype == FLASHDP_BF16 ? 0 : 1;
+    auto kern = which == 0 ? gram_norm_mfma_kernel<DT_BF16> : gram_norm_mfma_kernel<DT_F16>;
+    if (!attr_set[which]) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, GramCfg::LDS_BYTES);
+      if (e != hipSuccess) return e;
+      attr_set[which] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(GramCfg::NT), GramCfg::LDS_BYTES, st, g);
+  } else if (dtype == FLASHDP_BF16) {
+    hipLaunchKernelGGL((gram_norm_simple_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, g);
+  } else if (dtype == FLASHDP_F16) {
+    hipLaunchKernelGGL((gram_norm_simple_kernel<DT_F16>), dim3(grid), dim3(256), 0, st, g);
+  } else {
+    hipLaunchKernelGGL((gram_norm_simple_kernel<DT_F32>), dim3(grid), dim3(256), 0, st, g);
+  }
+  return hipGetLastError();
+}
+
 // ---- validation ----------------------------------------------------------------------------------
 
 int check_dims(int64_t B, int64_t T, int64_t P, int64_t D) {
@@ -260,13 +296,14 @@ int resolve_schedule(int schedule) {
     if (!std::strcmp(s, "scratch")) return FLASHDP_SCHEDULE_SCRATCH;
     if (!std::strcmp(s, "explicit")) return FLASHDP_SCHEDULE_EXPLICIT;
     if (!std::strcmp(s, "overlap")) return FLASHDP_SCHEDULE_OVERLAP;
+    if (!std::strcmp(s, "ghost")) return FLASHDP_SCHEDULE_GHOST;
   }
   return schedule;
 }
 
 size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mode) {
   const Plan p = make_plan(B, T, L.d_in, L.d_out, dtype);
-  return ws_layout(p, B, L.d_in, L.d_out, dtype, mode).total;
+  return ws_layout(p, B, T, L.d_in, L.d_out, dtype, mode).total;
 }
 
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; } } while (0)
@@ -280,13 +317,13 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mod
   const int stages = g_ctx.stages & parts;
   const int64_t P = L.d_in, D = L.d_out;
   const Plan plan = make_plan(B, T, P, D, dtype);
-  const WsLayout wl = ws_layout(plan, B, P, D, dtype, mode);
+  const WsLayout wl = ws_layout(plan, B, T, P, D, dtype, mode);
   GemmArgs a;
   a.X = L.X; a.dY = L.dY;
   a.B = (int)B; a.T = (int)T; a.P = (int)P; a.D = (int)D;
   a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
   a.partials = reinterpret_cast<float*>(ws + wl.partials);
-  a.scratch = mode != FLASHDP_SCHEDULE_TWOPASS ? (void*)(ws + wl.scratch) : nullptr;
+  a.scratch = (mode == FLASHDP_SCHEDULE_SCRATCH || mode == FLASHDP_SCHEDULE_EXPLICIT) ? (void*)(ws + wl.scratch) : nullptr;
   float* factors = reinterpret_cast<float*>(ws + wl.factors);
   a.factors = factors;
   a.out = L.out_grad;
@@ -323,9 +360,21 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mod
     if (stages & FLASHDP_STAGE_AGGREGATE)
       HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0, st, persistent_grid));
   } else {
-    if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
+    int n_partials = tiles;
+    if (mode == FLASHDP_SCHEDULE_GHOST) {
+      // norms from the Gram matrices (never stored): partials[B][blocks on or above the diagonal]
+      GramArgs g;
+      g.X = L.X; g.dY = L.dY; g.B = (int)B; g.T = (int)T; g.P = (int)P; g.D = (int)D;
+      g.nb = (int)gram_blocks(T, P, D, dtype);
+      g.n_tri = g.nb * (g.nb + 1) / 2;
+      g.partials = a.partials;
+      n_partials = g.n_tri;
+      if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gram(dtype, gram_mfma_ok(T, P, D, dtype), g, st));
+    } else if (stages & FLASHDP_STAGE_CONTRACT) {
+      HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
+    }
     if (stages & FLASHDP_STAGE_CLIP) {
-      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
+      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, n_partials, L.C, factors, L.out_norms);
       HIP_TRY(hipGetLastError());
     }
     if (stages & FLASHDP_STAGE_AGGREGATE) HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, st));
@@ -352,11 +401,16 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
   }
   if (workspace && !aligned16(workspace)) return FLASHDP_MISALIGNED;
   schedule = resolve_schedule(schedule);
-  size_t need_scratch = 0, need_small = 0, need_explicit = 0;
+  size_t need_scratch = 0, need_small = 0, need_explicit = 0, need_ghost = 0;
   for (int l = 0; l < n_layers; ++l) {
     need_scratch = std::max(need_scratch, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_SCRATCH));
     need_small = std::max(need_small, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_TWOPASS));
     need_explicit = std::max(need_explicit, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_EXPLICIT));
+    need_ghost = std::max(need_ghost, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_GHOST));
+    if (schedule == FLASHDP_SCHEDULE_GHOST) {   // grid of the Gram kernel
+      const int64_t nb = gram_blocks(T, layers[l].d_in, layers[l].d_out, dtype);
+      if (nb > 32768 || nb * (nb + 1) / 2 * B >= (int64_t(1) << 31)) return FLASHDP_UNSUPPORTED_SHAPE;   // 32-bit block arithmetic
+    }
   }
   int dev = 0;
   int st = device_or_error(&dev);
@@ -381,13 +435,13 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     }
     if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
     const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
-                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
+                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost : need_small;
     if (workspace_bytes < need) return FLASHDP_WORKSPACE_TOO_SMALL;
   } else {
     mode = schedule == FLASHDP_SCHEDULE_AUTO ? (overlap_ok ? FLASHDP_SCHEDULE_OVERLAP : FLASHDP_SCHEDULE_SCRATCH) : schedule;
     if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
     const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
-                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : need_small;
+                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost : need_small;
     void* p = nullptr; size_t got = 0;
     st = owned_workspace(need, &p, &got);
     if (st != FLASHDP_OK) return st;
@@ -443,7 +497,8 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     st = run_layer(layers[l], B, T, dtype, mode, ws, main_st, accumulate != 0, add_noise != 0);
     if (st != FLASHDP_OK) return st;
   }
-  g_ctx.last_schedule = mode == FLASHDP_SCHEDULE_SCRATCH ? "scratch" : mode == FLASHDP_SCHEDULE_EXPLICIT ? "explicit" : "twopass";
+  g_ctx.last_schedule = mode == FLASHDP_SCHEDULE_SCRATCH ? "scratch" : mode == FLASHDP_SCHEDULE_EXPLICIT ? "explicit"
+                        : mode == FLASHDP_SCHEDULE_GHOST ? "ghost" : "twopass";
   return FLASHDP_OK;
 }
 

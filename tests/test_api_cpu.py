@@ -83,6 +83,13 @@ def test_workspace_bytes_formula():
     assert F.flashdp_workspace_bytes([mk(5120, 13824)], B, T, F.F32, "scratch") >= B * 5120 * 13824 * 4
     assert 0 < F.flashdp_workspace_bytes([mk(5120, 13824)], B, T, F.BF16, "twopass") < (1 << 20)
     assert F.flashdp_workspace_bytes([mk(0, 8)], B, T, F.BF16, "scratch") == 0
+    # ghost-norm schedule: one partial per 128-row block pair on or above the diagonal (T = 2048: 136 per sample)
+    ghost = F.flashdp_workspace_bytes([mk(5120, 5120)], B, T, F.BF16, "ghost")
+    nb = (T + 127) // 128
+    assert B * max(nb * (nb + 1) // 2, 400) * 4 <= ghost < (1 << 20)
+    L = F.lib()
+    assert L.flashdp_set_schedule(5) == F.OK and L.flashdp_set_schedule(6) == F.INVALID_ARGUMENT
+    assert L.flashdp_set_schedule(0) == F.OK
 
 
 @pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a host without a GPU")

@@ -108,6 +108,17 @@ def test_explicit_four_stage_schedule_full_size_llama7b():
     check_layer(w, 0, X, dY, o0[0][0], o0[0][1], o1[0][0], used)
 
 
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("name", ["gpt2_small_mlp_up", "llama7b_q_proj"])
+def test_ghost_norm_schedule_full_size(name):
+    w = W.WORKLOADS[name]
+    host, o0, used = run_workload_sched(w, 0.0, "ghost")
+    _, o1, _ = run_workload_sched(w, w.sigma, "ghost")
+    assert used == "ghost"
+    X, dY = host[0]
+    check_layer(w, 0, X, dY, o0[0][0], o0[0][1], o1[0][0], used)
+
+
 def run_workload_sched(w, sigma, schedule):
     """run_workload with a workspace sized for the given schedule."""
     layers, host = [], []

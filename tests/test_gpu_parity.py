@@ -30,7 +30,7 @@ TOL_NORM_STATED = 5e-3
 
 
 def tight_tol(dtype, schedule):
-    if dtype == "fp32" or schedule in ("twopass", "explicit"):
+    if dtype == "fp32" or schedule in ("twopass", "explicit", "ghost"):
         return 5e-5
     return 4e-3   # the 16-bit scratch is bfloat16 for bf16 and for fp16 inputs
 
@@ -147,6 +147,48 @@ def test_f16_and_fp32_inputs(schedule, shape):
     X16, dY16 = X32.astype(np.float16), dY32.astype(np.float16)
     want = O.linear_dp_grad(X16.astype(np.float32), dY16.astype(np.float32), 1.0, 0.0, 9, 2)
     check_case(X16, dY16, 1.0, 1.0, 9, 2, "f16", schedule, oracle=want)
+
+
+# ---------------------------------------------------------------------------------------------------
+# ghost-norm schedule: norms from the two Gram matrices (never formed in memory), then the clipped accumulation
+# ---------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape", SMALL + [
+    (3, 300, 328, 520),      # 3 x 3 blocks of 128 rows: diagonal and off-diagonal blocks, ragged last block
+    (2, 513, 72, 40),        # long sequence, small features: the regime the identity is meant for
+    (2, 150, 77, 131),       # odd feature sizes: generic kernel, 64-row blocks, ragged
+])
+def test_ghost_norm_schedule_bf16(shape):
+    B, T, P, D = shape
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    e = check_case(X, dY, 1.0, 1.0, 11, 3, "bf16", "ghost")
+    print(shape, "ghost", e)
+
+
+@pytest.mark.parametrize("shape", [(3, 100, 136, 264), (2, 33, 50, 70), (2, 200, 128, 128)])
+def test_ghost_norm_schedule_f16_and_fp32(shape):
+    B, T, P, D = shape
+    rng = np.random.default_rng(B * T + 1)
+    X32 = rng.standard_normal((B, T, P)).astype(np.float32)
+    dY32 = (rng.standard_normal((B, T, D)) * 0.05 * (10.0 ** rng.uniform(-1, 1, size=(B, 1, 1)))).astype(np.float32)
+    check_case(X32, dY32, 1.0, 1.0, 9, 2, "fp32", "ghost")
+    X16, dY16 = X32.astype(np.float16), dY32.astype(np.float16)
+    want = O.linear_dp_grad(X16.astype(np.float32), dY16.astype(np.float32), 1.0, 0.0, 9, 2)
+    check_case(X16, dY16, 1.0, 1.0, 9, 2, "f16", "ghost", oracle=want)
+
+
+def test_ghost_norms_equal_contraction_norms_on_zero_and_single_token_samples():
+    # a sample of zeros has norm 0 (factor 1) by either route; T = 1 makes the Gram matrices 1 x 1
+    rng = np.random.default_rng(4)
+    X = W.float32_to_bf16_bits(rng.standard_normal((3, 1, 16)).astype(np.float32))
+    dY = W.float32_to_bf16_bits(rng.standard_normal((3, 1, 24)).astype(np.float32))
+    X[1] = 0
+    g, n, used = run_layer(X, dY, 1.0, 0.0, 1, 0, "ghost")
+    t, m, _ = run_layer(X, dY, 1.0, 0.0, 1, 0, "twopass")
+    assert used == "ghost" and n[1] == 0.0 and m[1] == 0.0
+    assert np.allclose(n, m, rtol=1e-6, atol=0) and rel_fro(g, t.astype(np.float64)) <= 1e-6
 
 
 def test_clip_branches_and_degenerate_inputs():
