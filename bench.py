@@ -162,7 +162,7 @@ def main():
     traffic_key = "scratch" if used == "overlap" else used
     n_launch = len(w.layers)
     roofline = {
-        "bound": "mfma", "kernel": "gemm_mfma_kernel (per-sample contraction + norm)",
+        "bound": "mfma", "kernel": "gemm_mfma_dma_kernel (per-sample contraction + norm + spill)",
         "achieved": round(flops / ms_contract / 1e9, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": round(flops / ms_contract / 1e9 / PEAK_BF16_TFLOPS, 4),
         "launches_per_step": n_launch, "avg_launch_ms": round(ms_contract / n_launch, 4),

@@ -43,8 +43,10 @@
  *
  * Environment overrides, read at every call (measurement aids, not needed in normal use):
  *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit | ghost   replaces the schedule argument;
- *   FLASHDP_TILE = 2 | 3 | 4     forces the matrix-core tile (256x256 with 64-deep k-tiles, 128x128,
- *                                256x256 with 32-deep k-tiles); -1 sends fp32 inputs to the generic kernel;
+ *   FLASHDP_TILE = 2 | 3 | 4 | 6 forces the matrix-core kernel (256x256 with 64-deep k-tiles, 128x128,
+ *                                256x256 with 32-deep k-tiles - these three stage tiles through registers -,
+ *                                256x256 with 32-deep k-tiles loaded straight into LDS);
+ *                                -1 sends fp32 inputs to the generic kernel;
  *   FLASHDP_OVERLAP_GRID = n     workgroups of the aggregation kernel in the overlapped schedule (512).
  */
 #ifndef FLASHDP_H

@@ -15,6 +15,7 @@
 
 #include "elementwise.hip.h"
 #include "gemm_mfma.hip.h"
+#include "gemm_mfma_dma.hip.h"
 #include "gemm_mfma_f32.hip.h"
 #include "gemm_simple.hip.h"
 #include "gram_norm.hip.h"
@@ -59,7 +60,9 @@ using Cfg256x8 = TileCfg<256, 256, 64, 2, 4>;   // 8 waves, 128x64 per wave
 using Cfg128x4 = TileCfg<128, 128, 64, 2, 2>;   // 4 waves, 64x64 per wave
 using Cfg256x8k32 = TileCfg<256, 256, 32, 2, 4>; // 8 waves, 32-deep k-tiles (half the LDS)
 
-enum Path { PATH_SIMPLE = 0, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5 };
+using CfgDma = DmaCfg<4>;                        // 8 waves, 32-deep k-tiles loaded straight into 4 LDS stages
+
+enum Path { PATH_SIMPLE = 0, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5, PATH_DMA = 6 };
 
 struct Plan {
   Path path;         // per-sample passes (norm, spill)
@@ -86,19 +89,18 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
     int choice = env_int("FLASHDP_TILE", 0);
-    if (choice < PATH_256x8 || choice > PATH_256x8k32) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
+    if (choice != PATH_DMA && (choice < PATH_256x8 || choice > PATH_256x8k32)) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
     if (choice == 0) {
       // enough 256x256 work items to fill 256 CUs a few times over, else the smaller tile.
-      // Measured on MI355X (Llama-13B up_proj, B = 8, norm pass): 8 waves of 128x64 with 32-deep k-tiles
-      // 1.16 PFLOP/s, with 64-deep k-tiles 1.05-1.10; 4 waves of 128x128 (one wave per SIMD) reached 0.96
-      // and spilled registers, and is no longer built.
+      // Measured on MI355X (Llama-13B block, B = 8, spill pass, N(0,1) data): 8 waves of 128x64 with 32-deep
+      // k-tiles loaded straight into LDS 1.22 PFLOP/s; the same tiling with the tiles staged through
+      // registers 1.07 (32-deep) resp. 1.0 (64-deep); 4 waves of 128x128 (one wave per SIMD) reached 0.96 and
+      // spilled registers, and is no longer built.  The register-staged kernels stay selectable (FLASHDP_TILE).
       const int64_t items = ((D + 255) / 256) * ((P + 255) / 256) * B;
-      choice = items >= 1024 ? PATH_256x8k32 : PATH_128x4;
+      choice = items >= 1024 ? PATH_DMA : PATH_128x4;
     }
     p.path = (Path)choice;
-    // The long K = B*T loop of the accumulating pass runs faster with 64-deep k-tiles (measured: 1.06 vs
-    // 0.94 PFLOP/s on up_proj), the per-sample passes with 32-deep ones (1.19 vs 1.10); same 256x256 tiling.
-    p.accum_path = (env_int("FLASHDP_TILE", 0) == 0 && p.path == PATH_256x8k32) ? PATH_256x8 : p.path;
+    p.accum_path = p.path;
     p.bm = p.bn = (p.path == PATH_128x4) ? 128 : 256;
   }
   p.tiles_m = (int)((D + p.bm - 1) / p.bm);
@@ -164,6 +166,18 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& a, hipStream_t st) {
       case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
       case PATH_256x8k32: return launch_mfma<Cfg256x8k32, MODE, DT>(a, st);
+      case PATH_DMA: {
+        static bool attr_set = false;
+        auto kern = gemm_mfma_dma_kernel<CfgDma, MODE, DT>;
+        if (!attr_set) {
+          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, CfgDma::LDS_BYTES);
+          if (e != hipSuccess) return e;
+          attr_set = true;
+        }
+        const int tiles_d = a.tiles_m * a.tiles_n;
+        hipLaunchKernelGGL(kern, dim3(MODE == MODE_ACCUM ? tiles_d : tiles_d * a.B), dim3(CfgDma::NT), CfgDma::LDS_BYTES, st, a);
+        return hipGetLastError();
+      }
       default: break;
     }
   }
@@ -420,7 +434,7 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
   bool overlap_ok = n_layers >= 2 && dtype != FLASHDP_F32 && g_ctx.stages == FLASHDP_STAGE_ALL;
   for (int l = 0; l < n_layers && overlap_ok; ++l) {
     const Plan p = make_plan(B, T, layers[l].d_in, layers[l].d_out, dtype);
-    overlap_ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
+    overlap_ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
   }
   const size_t slot = align_up(need_scratch, 256);
   const size_t need_overlap = 2 * slot;

@@ -162,6 +162,97 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
   *tn = r / rows;
 }
 
+// What a workgroup does with its finished tile.  acc[i][j][4q + r] =
+// G[m0 + wave_m*TM + 32i + lane%32][n0 + wave_n*TN + 32j + 8q + 4(lane/32) + r].  The caller has ended its main
+// loop with a barrier: the operand tiles in LDS are dead and LDS is reused for the reduction and the staging.
+template <typename Cfg, int MODE, int DT>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16_t (&acc)[Cfg::FM][Cfg::FN], unsigned short* lds,
+                                              int m0, int n0, int sample0, int tile, int tiles) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, FM = Cfg::FM, FN = Cfg::FN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % Cfg::WAVES_M, wave_n = wave / Cfg::WAVES_M;
+  const int row_base = m0 + wave_m * Cfg::TM + (lane & 31);
+  const int col_base = n0 + wave_n * Cfg::TN + 4 * (lane >> 5);
+  if constexpr (MODE == MODE_NORM || MODE == MODE_SPILL) {
+    // intra-block reduction of the squared norm: lane chain -> wave shuffle -> LDS across waves.
+    // Rows/columns beyond D/P were loaded as zeros and add nothing.
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) ss = fmaf(acc[i][j][e], acc[i][j][e], ss);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    // The operand tiles are dead after the barrier that follows the main loop; LDS now stages the
+    // 16-bit tile (row pitch BN + 8 elements) so that it leaves the chip in full rows, and holds the
+    // per-wave partial sums behind it.
+    constexpr int EP = BN + 8;                               // pitch in elements: 16-byte aligned rows
+    static_assert(BM * EP * 2 + 64 <= Cfg::LDS_BYTES, "epilogue staging must fit in the operand buffers");
+    float* red = (float*)(lds + BM * EP);
+    if (lane == 0) red[wave] = ss;
+    if constexpr (MODE == MODE_SPILL) {
+      unsigned short* st = lds + (wave_m * Cfg::TM + (lane & 31)) * EP + wave_n * Cfg::TN + 4 * (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            uint2 v;
+            // the scratch is bfloat16 for fp16 inputs too: a per-sample gradient before clipping has no
+            // bound, and fp16's range (65504) would turn a large one into inf
+            v.x = pack2_16bit<DT_BF16>(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+            v.y = pack2_16bit<DT_BF16>(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            *(uint2*)(st + (i * 32) * EP + j * 32 + 8 * q) = v;
+          }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      float tot = 0.0f;
+      for (int w = 0; w < NT / 64; ++w) tot += red[w];
+      a.partials[(size_t)sample0 * tiles + tile] = tot;
+    }
+    if constexpr (MODE == MODE_SPILL) {
+      // 16 bytes per lane, BN/8 lanes per row: every store instruction writes whole 2*BN-byte rows
+      unsigned short* sc = (unsigned short*)a.scratch + (size_t)sample0 * a.D * a.P;
+      constexpr int CPR = BN / 8;
+#pragma unroll
+      for (int it = 0; it < BM * CPR / NT; ++it) {
+        const int c = tid + it * NT;
+        const int r = c / CPR, cc = c % CPR;
+        const int row = m0 + r, col = n0 + cc * 8;
+        if (row < a.D && col < a.P)   // P is a multiple of 8 on this path: a chunk is all in or all out
+          *(u32x4_t*)(sc + (size_t)row * a.P + col) = *(const u32x4_t*)(lds + r * EP + cc * 8);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row = row_base + i * 32;
+      if (row >= a.D) continue;
+      float* obase = a.out;
+      if constexpr (MODE == MODE_MATERIALIZE) obase = (float*)a.scratch + (size_t)sample0 * a.D * a.P;
+      float* prow = obase + (size_t)row * a.P;
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = col_base + j * 32 + 8 * q;
+          if (col < a.P) {
+            float4 v = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            if (MODE == MODE_ACCUM && a.accumulate) {
+              const float4 o = *(const float4*)(prow + col);
+              v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+            }
+            *(float4*)(prow + col) = v;
+          }
+        }
+    }
+  }
+}
+
 template <typename Cfg, int MODE, int DT>
 __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(const GemmArgs a) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NT = Cfg::NT;
@@ -323,87 +414,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_kernel(c
   }
   __syncthreads();   // the reduction below reuses the LDS tiles
 
-  // ---- epilogue.  acc[i][j][4q + r] = G[m0 + wave_m*TM + 32i + lane%32][n0 + wave_n*TN + 32j + 8q + 4(lane/32) + r]
-  const int row_base = m0 + wave_m * Cfg::TM + (lane & 31);
-  const int col_base = n0 + wave_n * Cfg::TN + 4 * (lane >> 5);
-  if constexpr (MODE == MODE_NORM || MODE == MODE_SPILL) {
-    // intra-block reduction of the squared norm: lane chain -> wave shuffle -> LDS across waves.
-    // Rows/columns beyond D/P were loaded as zeros and add nothing.
-    float ss = 0.0f;
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) ss = fmaf(acc[i][j][e], acc[i][j][e], ss);
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-    // The operand tiles are dead after the barrier that follows the main loop; LDS now stages the
-    // 16-bit tile (row pitch BN + 8 elements) so that it leaves the chip in full rows, and holds the
-    // per-wave partial sums behind it.
-    constexpr int EP = BN + 8;                               // pitch in elements: 16-byte aligned rows
-    static_assert(BM * EP * 2 + 64 <= Cfg::LDS_BYTES, "epilogue staging must fit in the operand buffers");
-    float* red = (float*)(lds + BM * EP);
-    if (lane == 0) red[wave] = ss;
-    if constexpr (MODE == MODE_SPILL) {
-      unsigned short* st = lds + (wave_m * Cfg::TM + (lane & 31)) * EP + wave_n * Cfg::TN + 4 * (lane >> 5);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            uint2 v;
-            // the scratch is bfloat16 for fp16 inputs too: a per-sample gradient before clipping has no
-            // bound, and fp16's range (65504) would turn a large one into inf
-            v.x = pack2_16bit<DT_BF16>(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
-            v.y = pack2_16bit<DT_BF16>(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-            *(uint2*)(st + (i * 32) * EP + j * 32 + 8 * q) = v;
-          }
-    }
-    __syncthreads();
-    if (tid == 0) {
-      float tot = 0.0f;
-      for (int w = 0; w < NT / 64; ++w) tot += red[w];
-      a.partials[(size_t)sample0 * tiles + tile] = tot;
-    }
-    if constexpr (MODE == MODE_SPILL) {
-      // 16 bytes per lane, BN/8 lanes per row: every store instruction writes whole 2*BN-byte rows
-      unsigned short* sc = (unsigned short*)a.scratch + (size_t)sample0 * a.D * a.P;
-      constexpr int CPR = BN / 8;
-#pragma unroll
-      for (int it = 0; it < BM * CPR / NT; ++it) {
-        const int c = tid + it * NT;
-        const int r = c / CPR, cc = c % CPR;
-        const int row = m0 + r, col = n0 + cc * 8;
-        if (row < a.D && col < a.P)   // P is a multiple of 8 on this path: a chunk is all in or all out
-          *(u32x4_t*)(sc + (size_t)row * a.P + col) = *(const u32x4_t*)(lds + r * EP + cc * 8);
-      }
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-      const int row = row_base + i * 32;
-      if (row >= a.D) continue;
-      float* obase = a.out;
-      if constexpr (MODE == MODE_MATERIALIZE) obase = (float*)a.scratch + (size_t)sample0 * a.D * a.P;
-      float* prow = obase + (size_t)row * a.P;
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = col_base + j * 32 + 8 * q;
-          if (col < a.P) {
-            float4 v = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-            if (MODE == MODE_ACCUM && a.accumulate) {
-              const float4 o = *(const float4*)(prow + col);
-              v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-            }
-            *(float4*)(prow + col) = v;
-          }
-        }
-    }
-  }
+  tile_epilogue<Cfg, MODE, DT>(a, acc, lds, m0, n0, sample0, tile, tiles);
 }
 
 }  // namespace flashdp

@@ -118,7 +118,7 @@ SMALL = [
 
 @pytest.mark.parametrize("shape", SMALL)
 @pytest.mark.parametrize("schedule", ["twopass", "scratch", "explicit"])
-@pytest.mark.parametrize("tile", [2, 3, 4])
+@pytest.mark.parametrize("tile", [2, 3, 4, 6])
 def test_small_bf16_all_tiles(shape, schedule, tile):
     B, T, P, D = shape
     base = W.WORKLOADS["gpt2_small_mlp_up"]
