@@ -111,9 +111,11 @@ __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch
       acc[4 + q] = fmaf(noise_scale, z1.z[q], acc[4 + q]);
     }
   }
-  float4* dst = (float4*)out + 2 * v;
-  dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-  dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  f32x4_t* dst = (f32x4_t*)out + 2 * v;
+  const f32x4_t lo = {acc[0], acc[1], acc[2], acc[3]}, hi = {acc[4], acc[5], acc[6], acc[7]};
+  __builtin_nontemporal_store(lo, dst);
+  __builtin_nontemporal_store(hi, dst + 1);
 }
 
 // Generic version: any scratch type, any S; one Philox group (4 elements) per thread.

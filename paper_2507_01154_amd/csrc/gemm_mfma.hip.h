@@ -224,7 +224,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16_t (&acc)
         const int r = c / CPR, cc = c % CPR;
         const int row = m0 + r, col = n0 + cc * 8;
         if (row < a.D && col < a.P)   // P is a multiple of 8 on this path: a chunk is all in or all out
-          *(u32x4_t*)(sc + (size_t)row * a.P + col) = *(const u32x4_t*)(lds + r * EP + cc * 8);
+          __builtin_nontemporal_store(*(const u32x4_t*)(lds + r * EP + cc * 8), (u32x4_t*)(sc + (size_t)row * a.P + col));
       }
     }
   } else {
