@@ -81,6 +81,22 @@ def time_events(fn, steps, warmup):
     return s.elapsed_time(e) / steps
 
 
+def time_each(fn, steps, warmup):
+    """Device time of every single call (events on the current stream between calls): (median, min) in ms."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for k in range(steps):
+        fn()
+        ev[k + 1].record()
+    torch.cuda.synchronize()
+    ts = sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(steps))
+    return ts[len(ts) // 2], ts[0]
+
+
 def cpu_baseline(w, target_flop=6e12):
     """The oracle as it stands on the host cores, on a bounded sample of the same workload: whole layers
     (all samples, full T), largest first, until about target_flop of work (10-30 s) has been timed."""
@@ -147,6 +163,7 @@ def main():
     used = F.flashdp_last_schedule()
     flops = float(w.flops())
     tflops = flops / ms / 1e9
+    ms_median, ms_min = time_each(step, args.steps, 2)   # spread of single steps, outside the timed region above
 
     # dominant kernel alone (the per-sample contraction + intra-block norm), same launches, same stream
     F.flashdp_set_stages(F.STAGE_CONTRACT)
@@ -181,6 +198,7 @@ def main():
         "config": {"workload": w.name, "B": w.B, "T": w.T,
                    "layers": [f"{s.name}:{s.d_in}->{s.d_out}" for s in w.layers],
                    "C": w.C, "sigma": w.sigma, "schedule": used},
+        "ms_per_step_median": round(ms_median, 4), "ms_per_step_min": round(ms_min, 4),
         "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "hardware_flops_per_step": hw_flops,
         "stage_ms": {"contract": round(ms_contract, 4), "aggregate_and_noise": round(ms_aggregate, 4)},

@@ -412,3 +412,24 @@ def test_twenty_runs_are_bit_identical(schedule):
     for _ in range(19):
         again = run_layer(X, dY, 1.0, 1.0, 3, 2, schedule)
         assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+
+
+@pytest.mark.parametrize("schedule", ["scratch", "twopass"])
+def test_large_shape_kernel_is_bit_repeatable_and_matches_the_register_staged_one(schedule):
+    # a shape big enough for the default path to pick the direct-to-LDS kernel (1024 work items of 256 x 256):
+    # ten runs bit-identical (its loads are waited for by hand: a missed wait would show as run-to-run noise),
+    # and the same numbers as the register-staged kernel, which computes every element in the same order
+    rng = np.random.default_rng(5)
+    B, T, P, D = 4, 96, 4096, 4096
+    X = W.float32_to_bf16_bits(rng.standard_normal((B, T, P)).astype(np.float32))
+    dY = W.float32_to_bf16_bits((rng.standard_normal((B, T, D)) * 0.01).astype(np.float32))
+    first = run_layer(X, dY, 1.0, 0.0, 3, 2, schedule)
+    for _ in range(9):
+        again = run_layer(X, dY, 1.0, 0.0, 3, 2, schedule)
+        assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+    staged = run_layer(X, dY, 1.0, 0.0, 3, 2, schedule, tile=4)
+    assert np.array_equal(first[1], staged[1])
+    assert np.array_equal(first[0], staged[0]) or rel_fro(first[0], staged[0].astype(np.float64)) <= 1e-6
+    want, wn = O.linear_dp_grad(X, dY, 1.0, 0.0, 3, 2)
+    assert np.max(np.abs(first[1] - wn) / wn) <= 1e-4
+    assert rel_fro(first[0], want) <= tight_tol("bf16", schedule)
