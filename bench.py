@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-schedule-comparison", action="store_true",
                     help="skip timing the other schedules (two-pass recompute, explicit four-stage) beside the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--share-x", action="store_true",
+                    help="secondary variant: q/k/v (and gate/up) read the same X tensor, as in a real decoder block; "
+                         "the default gives every layer its own tensors, as the workload states")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy: a kernel of known traffic to scale profiler byte counters by")
@@ -142,8 +145,13 @@ def main():
     dev = "cuda:0"
     dtype_code = F.BF16 if w.dtype == "bf16" else F.F32
     layers, keep = [], []
+    shared = {}
     for l, spec in enumerate(w.layers):
         X, dY = W.make_layer_device(w, l, dev)
+        if args.share_x:
+            group = {"q_proj": "attn", "k_proj": "attn", "v_proj": "attn", "gate_proj": "mlp", "up_proj": "mlp"}.get(spec.name)
+            if group is not None:
+                X = shared.setdefault(group, X)
         out = torch.empty((spec.d_out, spec.d_in), dtype=torch.float32, device=dev)
         norms = torch.empty((w.B,), dtype=torch.float32, device=dev)
         layers.append(dict(X=X, dY=dY, d_in=spec.d_in, d_out=spec.d_out, C=w.C, sigma=w.sigma,
@@ -197,7 +205,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "T": w.T,
                    "layers": [f"{s.name}:{s.d_in}->{s.d_out}" for s in w.layers],
-                   "C": w.C, "sigma": w.sigma, "schedule": used},
+                   "C": w.C, "sigma": w.sigma, "schedule": used, "shared_x": bool(args.share_x)},
         "ms_per_step_median": round(ms_median, 4), "ms_per_step_min": round(ms_min, 4),
         "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "hardware_flops_per_step": hw_flops,
