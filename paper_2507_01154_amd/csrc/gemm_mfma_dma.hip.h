@@ -22,6 +22,7 @@
 #include <stdint.h>
 
 #include "gemm_mfma.hip.h"
+#include "lds_plan.h"
 
 namespace flashdp {
 
@@ -32,6 +33,8 @@ struct DmaCfg {
   static constexpr int NT = 64 * WAVES_M * WAVES_N;
   static constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N, FM = TM / 32, FN = TN / 32;
   static constexpr int A_ELEMS = BK * BM, B_ELEMS = BK * BN, STAGE_ELEMS = A_ELEMS + B_ELEMS;
+  static_assert(A_ELEMS == lds_plan::OPERAND_ELEMS && B_ELEMS == lds_plan::OPERAND_ELEMS && STAGE_ELEMS == lds_plan::STAGE_ELEMS &&
+                BM == lds_plan::ROW && BK == lds_plan::TILE_ROWS, "the index arithmetic in lds_plan.h is written for this tile");
   static constexpr int OPERAND_BYTES = STAGES * STAGE_ELEMS * 2;
   static constexpr int EPILOGUE_BYTES = BM * (BN + 8) * 2 + 64;
   static constexpr int LDS_BYTES = OPERAND_BYTES > EPILOGUE_BYTES ? OPERAND_BYTES : EPILOGUE_BYTES;
@@ -86,8 +89,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kern
   const int m0 = tm * BM, n0 = tn * BN;
 
   // ---- direct-load plan: this wave fills rows 2 wave, 2 wave + 1 (first instruction) and 16 more (second)
-  const int d_row = 2 * wave + (lane >> 5);
-  const int d_chunk = (lane & 31) ^ ((d_row & 3) << 2);   // the chunk of the row this lane fetches (swizzle)
+  const int d_row = lds_plan::load_row(wave, lane);
+  const int d_chunk = lds_plan::load_chunk(wave, lane);   // the chunk of the row this lane fetches (swizzle)
   const bool a_ok = m0 + d_chunk * 8 < a.D;
   const bool b_ok = n0 + d_chunk * 8 < a.P;
   // byte offsets inside one sample; an out-of-range column is sent to 2 GiB, beyond num_records, and reads 0
@@ -97,7 +100,6 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kern
   const uint32_t a_kstep = (uint32_t)(BK * a.D) * 2u, b_kstep = (uint32_t)(BK * a.P) * 2u;
   const uint32_t a_bytes = (uint32_t)a.T * (uint32_t)a.D * 2u, b_bytes = (uint32_t)a.T * (uint32_t)a.P * 2u;
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned short*)lds;
-  const uint32_t d_lds = lds_base + (uint32_t)(2 * wave) * (ROW * 2);   // first instruction, operand A, stage 0
 
   const int kt_per_sample = (a.T + BK - 1) / BK;
   const int nk = kt_per_sample * n_samples;
@@ -109,11 +111,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kern
     const char* pb = (const char*)a.X + (size_t)(sample0 + ld_s) * b_bytes;
     const u32x4_t rsa = make_rsrc_words(pa, a_bytes), rsb = make_rsrc_words(pb, b_bytes);
     const uint32_t ao = a_off0 + (uint32_t)ld_kt * a_kstep, bo = b_off0 + (uint32_t)ld_kt * b_kstep;
-    const uint32_t dst = d_lds + (uint32_t)stage * (Cfg::STAGE_ELEMS * 2);
-    load_to_lds(rsa, ao, dst);
-    load_to_lds(rsa, ao + a_half, dst + 16 * ROW * 2);
-    load_to_lds(rsb, bo, dst + Cfg::A_ELEMS * 2);
-    load_to_lds(rsb, bo + b_half, dst + Cfg::A_ELEMS * 2 + 16 * ROW * 2);
+    load_to_lds(rsa, ao, lds_base + lds_plan::load_dst_bytes(stage, 0, wave, 0));
+    load_to_lds(rsa, ao + a_half, lds_base + lds_plan::load_dst_bytes(stage, 0, wave, 1));
+    load_to_lds(rsb, bo, lds_base + lds_plan::load_dst_bytes(stage, 1, wave, 0));
+    load_to_lds(rsb, bo + b_half, lds_base + lds_plan::load_dst_bytes(stage, 1, wave, 1));
     ld_kt += 1;
     const bool wrap = ld_kt >= kt_per_sample && ld_s + 1 < n_samples;
     ld_s = wrap ? ld_s + 1 : ld_s;
@@ -121,14 +122,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kern
   };
 
   // ---- fragment read plan: as in gemm_mfma_kernel, with the 32-column block index XORed by (row & 3)
-  const int f_row = 8 * (lane >> 5) + ((lane & 15) >> 2);
-  const int f_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const int r3 = (lane & 15) >> 2;   // == f_row & 3, also for the rows + 4, + 16 the reads below add
   int a_rd[FM], b_rd[FN];
 #pragma unroll
-  for (int i = 0; i < FM; ++i) a_rd[i] = f_row * ROW + ((wave_m * FM + i) ^ r3) * 32 + f_col;
+  for (int i = 0; i < FM; ++i) a_rd[i] = lds_plan::frag_offset(lane, wave_m * FM + i);
 #pragma unroll
-  for (int j = 0; j < FN; ++j) b_rd[j] = Cfg::A_ELEMS + f_row * ROW + ((wave_n * FN + j) ^ r3) * 32 + f_col;
+  for (int j = 0; j < FN; ++j) b_rd[j] = Cfg::A_ELEMS + lds_plan::frag_offset(lane, wave_n * FN + j);
 
   f32x16_t acc[FM][FN];
 #pragma unroll
