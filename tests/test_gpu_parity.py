@@ -433,3 +433,27 @@ def test_large_shape_kernel_is_bit_repeatable_and_matches_the_register_staged_on
     want, wn = O.linear_dp_grad(X, dY, 1.0, 0.0, 3, 2)
     assert np.max(np.abs(first[1] - wn) / wn) <= 1e-4
     assert rel_fro(first[0], want) <= tight_tol("bf16", schedule)
+
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 6)), int(rng.integers(1, 300)), 8 * int(rng.integers(1, 76)), 8 * int(rng.integers(1, 76)))
+            for _ in range(n)]
+
+
+@pytest.mark.parametrize("shape", _random_shapes(12, 2024))
+@pytest.mark.parametrize("tile", [4, 6])
+def test_random_shapes_both_kernel_families(shape, tile):
+    # seeded random (B, T, d_in, d_out) with ragged tiles in every dimension, through the register-staged and the
+    # direct-to-LDS kernel; scratch schedule (norm + spill + aggregation) and the plain batch gradient
+    B, T, P, D = shape
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    check_case(X, dY, 1.0, 0.7, 17, 5, "bf16", "scratch", tile=tile)
+    out = torch.full((D, P), float("nan"), device=DEV)
+    with env(FLASHDP_TILE=tile):
+        F.flashdp_plain_grad(to_device(X), to_device(dY), B, T, P, D, F.BF16, out)
+    torch.cuda.synchronize()
+    want, _ = O.linear_dp_grad(X, dY, 1e30, 0.0, 0, 0)      # nothing clips: the plain batch gradient
+    assert rel_fro(out.cpu().numpy(), want) <= 5e-5
