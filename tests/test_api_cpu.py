@@ -114,3 +114,38 @@ def test_header_is_plain_c_and_links(tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0, r.stdout + r.stderr
     assert r.stdout.split()[0] == str(F.flashdp_version())
+
+
+def test_register_budget_of_the_overlapped_schedule():
+    """The overlapped schedule runs two 4-wave aggregation workgroups per CU beside one resident 8-wave
+    contraction workgroup.  That only fits while, per SIMD, 2 contraction waves + 2 aggregation waves stay within
+    the 512 vector registers (allocated in blocks of 8); a contraction kernel grown to 218 registers measured
+    4 % slower end to end for this reason alone.  Checked from the compiler's own resource report."""
+    import re
+    import subprocess
+    import tempfile
+    from paper_2507_01154_amd import build as B
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), "--offload-arch=gfx950", "-O3", "-std=c++17",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "--cuda-device-only", "-c",
+               "-Rpass-analysis=kernel-resource-usage", B.sources()[0], "-o", os.path.join(tmp, "api.o")]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    usage, cur = {}, None
+    for line in res.stderr.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            cur = m.group(1)
+            usage[cur] = {}
+        m = re.search(r"remark:\s+(VGPRs|AGPRs|VGPRs Spill|SGPRs Spill|ScratchSize \[bytes/lane\]): (\d+)", line)
+        if m and cur:
+            usage[cur][m.group(1)] = int(m.group(2))
+    up8 = lambda n: (n + 7) // 8 * 8
+    spill = [k for k in usage if "gemm_mfma_dma_kernel" in k and "ELi1ELi" in k]          # MODE_SPILL, bf16 and f16
+    agg = [k for k in usage if "aggregate16_persistent_kernel" in k]
+    assert len(spill) == 2 and len(agg) == 1
+    for k in spill:
+        assert 2 * up8(usage[k]["VGPRs"] + usage[k]["AGPRs"]) + 2 * up8(usage[agg[0]]["VGPRs"]) <= 512, (k, usage[k], usage[agg[0]])
+    # and no kernel of the library spills registers to memory
+    for k, u in usage.items():
+        assert u.get("VGPRs Spill", 0) == 0 and u.get("ScratchSize [bytes/lane]", 0) == 0, (k, u)
