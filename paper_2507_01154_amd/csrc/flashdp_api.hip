@@ -69,6 +69,7 @@ struct Plan {
   Path accum_path;   // batch-accumulating pass (second pass of the two-pass schedule, plain gradient)
   int bm, bn;
   int tiles_m, tiles_n;
+  int accum_tiles_m, accum_tiles_n;   // the accumulating pass has one workgroup per tile (not per sample and tile)
 };
 
 int env_int(const char* name, int dflt) {
@@ -91,20 +92,28 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     int choice = env_int("FLASHDP_TILE", 0);
     if (choice != PATH_DMA && (choice < PATH_256x8 || choice > PATH_256x8k32)) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
     if (choice == 0) {
-      // enough 256x256 work items to fill 256 CUs a few times over, else the smaller tile.
-      // Measured on MI355X (Llama-13B block, B = 8, spill pass, N(0,1) data): 8 waves of 128x64 with 32-deep
+      // The 256x256 direct-to-LDS kernel unless the problem has too few such work items to occupy the chip:
+      // measured on MI355X (scratch schedule, T = 1024..2048, features 768..13824, B = 1..8) it beats the
+      // 128x128 register-staged kernel by 20-35 % from about 140 work items up (half the CUs busy), ties around
+      // 70-130, and loses below (36 items: 160 vs 206 TFLOP/s).
+      // Llama-13B block, B = 8, spill pass, N(0,1) data: 8 waves of 128x64 with 32-deep
       // k-tiles loaded straight into LDS 1.22 PFLOP/s; the same tiling with the tiles staged through
       // registers 1.07 (32-deep) resp. 1.0 (64-deep); 4 waves of 128x128 (one wave per SIMD) reached 0.96 and
       // spilled registers, and is no longer built.  The register-staged kernels stay selectable (FLASHDP_TILE).
       const int64_t items = ((D + 255) / 256) * ((P + 255) / 256) * B;
-      choice = items >= 1024 ? PATH_DMA : PATH_128x4;
+      choice = items >= 128 ? PATH_DMA : PATH_128x4;
     }
     p.path = (Path)choice;
     p.accum_path = p.path;
+    // ... so it needs about the same number of 256x256 tiles by itself before the large tile pays
+    if (env_int("FLASHDP_TILE", 0) == 0 && p.path == PATH_DMA && ((D + 255) / 256) * ((P + 255) / 256) < 128) p.accum_path = PATH_128x4;
     p.bm = p.bn = (p.path == PATH_128x4) ? 128 : 256;
   }
   p.tiles_m = (int)((D + p.bm - 1) / p.bm);
   p.tiles_n = (int)((P + p.bn - 1) / p.bn);
+  const int abm = (p.accum_path == p.path) ? p.bm : 128, abn = (p.accum_path == p.path) ? p.bn : 128;
+  p.accum_tiles_m = (int)((D + abm - 1) / abm);
+  p.accum_tiles_n = (int)((P + abn - 1) / abn);
   return p;
 }
 
@@ -160,7 +169,9 @@ hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
 }
 
 template <int MODE, int DT>
-hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& a, hipStream_t st) {
+hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& args, hipStream_t st) {
+  GemmArgs a = args;
+  if (MODE == MODE_ACCUM) { a.tiles_m = p.accum_tiles_m; a.tiles_n = p.accum_tiles_n; }
   if constexpr (DT != DT_F32) {
     switch (MODE == MODE_ACCUM ? p.accum_path : p.path) {
       case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
