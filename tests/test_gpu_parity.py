@@ -457,3 +457,16 @@ def test_random_shapes_both_kernel_families(shape, tile):
     torch.cuda.synchronize()
     want, _ = O.linear_dp_grad(X, dY, 1e30, 0.0, 0, 0)      # nothing clips: the plain batch gradient
     assert rel_fro(out.cpu().numpy(), want) <= 5e-5
+
+
+@pytest.mark.parametrize("shape", [(64, 40, 512, 512), (3, 2100, 1024, 776), (9, 130, 1032, 1288), (2, 4000, 776, 1024)])
+@pytest.mark.parametrize("schedule", ["auto", "twopass", "ghost"])
+def test_medium_shapes_default_kernel_choice(shape, schedule):
+    # shapes with enough 256 x 256 work items for the default choice to be the direct-to-LDS kernel: many
+    # samples, a long ragged T, ragged feature sizes
+    B, T, P, D = shape
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    e = check_case(X, dY, 1.0, 1.0, 23, 1, "bf16", schedule)
+    print(shape, schedule, e)
