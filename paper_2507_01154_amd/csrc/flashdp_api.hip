@@ -43,7 +43,7 @@ std::map<int, OwnedWs> g_owned;   // device -> library-owned workspace
 // Per-device second stream and events of the overlapped schedule (default priority, created on first use).
 struct SideStream {
   hipStream_t stream = nullptr;
-  std::vector<hipEvent_t> ready, done;   // per layer slot: clip factors ready / aggregation done
+  std::vector<hipEvent_t> ready, done;   // per layer slot: contraction done / aggregation done
 };
 std::map<int, SideStream> g_side;
 std::mutex g_side_mutex;
@@ -474,8 +474,8 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
   }
   hipStream_t main_st = static_cast<hipStream_t>(stream);
   if (mode == FLASHDP_SCHEDULE_OVERLAP) {
-    // Layer l: contraction + clip factors on the caller's stream into scratch slot l % 2; its aggregation
-    // on the side stream, beside the contraction of layer l+1.  Events order the two streams; the caller's
+    // Layer l: contraction on the caller's stream into scratch slot l % 2; its clip factors and aggregation
+    // on the side stream, beside the contraction of layer l+1 (which then follows layer l's back to back).  Events order the two streams; the caller's
     // stream waits for the last aggregations before the call's work counts as complete.
     // The side stream and its events are shared by every thread using this device: the whole enqueue
     // sequence below is done under the lock, so that one call's record/wait pairs are never interleaved
@@ -503,13 +503,13 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
       char* wsl = ws + (size_t)(l & 1) * slot;
       if (l >= 2) HIP_TRY(hipStreamWaitEvent(main_st, side->done[l - 2], 0));   // slot free again
       st = run_layer(Lr, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, main_st, accumulate != 0, add_noise != 0,
-                     FLASHDP_STAGE_CONTRACT | FLASHDP_STAGE_CLIP);
+                     FLASHDP_STAGE_CONTRACT);
       if (st != FLASHDP_OK) return st;
       HIP_TRY(hipEventRecord(side->ready[l], main_st));
       HIP_TRY(hipStreamWaitEvent(side->stream, side->ready[l], 0));
       // the last layer has nothing to hide behind: ordinary grid
       st = run_layer(Lr, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, side->stream, accumulate != 0, add_noise != 0,
-                     FLASHDP_STAGE_AGGREGATE, l + 1 < n_layers ? grid : 0);
+                     FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE, l + 1 < n_layers ? grid : 0);
       if (st != FLASHDP_OK) return st;
       HIP_TRY(hipEventRecord(side->done[l], side->stream));
     }
