@@ -100,6 +100,19 @@ def time_each(fn, steps, warmup):
     return ts[len(ts) // 2], ts[0]
 
 
+def mfma_only(F, torch, dev):
+    """The matrix cores alone (register-resident operands, the contraction kernel's instruction mix, no memory):
+    what this part sustains on all-zero and on random operands, in TFLOP/s.  ~0.1 s of GPU time each."""
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    wgs, iters = 1024, 20000
+    flop = wgs * 8 * iters * 16 * 32768.0
+    out = {}
+    for name, pattern in (("zeros", 0), ("random", 1)):
+        ms = time_events(lambda: F.flashdp_mfma_probe(pattern, iters, wgs, sink), 3, 2)
+        out[name + "_tflops"] = round(flop / ms / 1e9, 1)
+    return out
+
+
 def cpu_baseline(w, target_flop=6e12):
     """The oracle as it stands on the host cores, on a bounded sample of the same workload: whole layers
     (all samples, full T), largest first, until about target_flop of work (10-30 s) has been timed."""
@@ -193,6 +206,10 @@ def main():
         "launches_per_step": n_launch, "avg_launch_ms": round(ms_contract / n_launch, 4),
         "flops_per_launch": flops / n_launch, "traffic": None,
     }
+    if w.dtype == "bf16":
+        probe = mfma_only(F, torch, dev)
+        roofline["mfma_only"] = probe
+        roofline["frac_of_mfma_only_random"] = round(flops / ms_contract / 1e9 / probe["random_tflops"], 4)
     mt = MEASURED_TRAFFIC.get((w.name, traffic_key))
     if mt:
         roofline["traffic"] = mt["read_bytes"] + mt["write_bytes"]

@@ -167,6 +167,14 @@ int flashdp_set_dtype(int dtype);
 int flashdp_set_layer(uint32_t layer);
 int flashdp_set_schedule(int schedule);
 
+/* Measurement aid, not a step of the method: runs the matrix-core instruction mix of the contraction kernel's
+ * inner loop (bf16, 32x32x16, eight accumulators per wave) on register-resident operands - no memory, no LDS,
+ * no barrier - so that a benchmark can quote the rate this part actually sustains next to the nominal peak.
+ * pattern 0 = all-zero operands, 1 = pseudo-random operands; `workgroups` workgroups of 8 waves, each wave
+ * issuing 16 * iters instructions of 32768 FLOP; sink (device, 4 bytes) is never written in practice.
+ * INVALID_ARGUMENT for other patterns, iters or workgroups <= 0 or absurdly large, or a null sink. */
+int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream);
+
 /* Measurement aid: which stages of Algorithm 1 the following calls on this thread enqueue (default: all).
  * With a partial mask the outputs are not meaningful; the stages left out read whatever the workspace
  * holds from an earlier full call.  CONTRACT = per-sample contraction + intra-block norm (the dominant

@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.flashdp_noise_field.restype = ci
         L.flashdp_box_muller.argtypes = [vp, i64, vp, vp]
         L.flashdp_box_muller.restype = ci
+        L.flashdp_mfma_probe.argtypes = [ci, ci, ci, vp, vp]
+        L.flashdp_mfma_probe.restype = ci
         L.flashdp_set_stream.argtypes = [vp]
         L.flashdp_set_workspace.argtypes = [vp, sz]
         L.flashdp_set_dtype.argtypes = [ci]
@@ -219,3 +221,8 @@ def flashdp_noise_field(seed: int, layer: int, n: int, z, stream=None):
 
 def flashdp_box_muller(words, n_groups: int, z, stream=None):
     _check(lib().flashdp_box_muller(_ptr(words), n_groups, _ptr(z), _stream_handle(stream)), "flashdp_box_muller")
+
+
+def flashdp_mfma_probe(pattern: int, iters: int, workgroups: int, sink, stream=None):
+    _check(lib().flashdp_mfma_probe(int(pattern), int(iters), int(workgroups), _ptr(sink), _stream_handle(stream)),
+           "flashdp_mfma_probe")

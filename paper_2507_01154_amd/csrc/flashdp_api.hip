@@ -19,6 +19,7 @@
 #include "gemm_mfma_f32.hip.h"
 #include "gemm_simple.hip.h"
 #include "gram_norm.hip.h"
+#include "mfma_probe.hip.h"
 
 using namespace flashdp;
 
@@ -589,6 +590,17 @@ int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* 
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
   hipLaunchKernelGGL(box_muller_kernel, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream), words, (size_t)n_groups, z);
+  HIP_TRY(hipGetLastError());
+  return FLASHDP_OK;
+}
+
+int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream) {
+  if ((pattern != 0 && pattern != 1) || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
+    return FLASHDP_INVALID_ARGUMENT;
+  int dev = 0;
+  int st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), pattern, iters, sink);
   HIP_TRY(hipGetLastError());
   return FLASHDP_OK;
 }

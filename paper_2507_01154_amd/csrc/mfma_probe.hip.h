@@ -1,0 +1,61 @@
+// Measurement aid, not part of Algorithm 1: what the matrix cores of this part deliver when nothing else is
+// in the way.  Every wave runs the instruction mix of the contraction kernel's inner loop - eight 32x32
+// accumulators, four "row" and two "column" operand fragments, two fragment sets used in turn - with all
+// operands resident in registers: no LDS, no memory, no barrier.  With all-zero operands the result is the
+// part's issue-limited rate; with random operands it is the rate the part sustains once its clock has
+// settled under a bit-toggling load, which is the ceiling any real contraction on such data runs under.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_mfma.hip.h"
+
+namespace flashdp {
+
+// pattern 0: zeros; 1: pseudo-random bf16 values in (-2, 2) made from a hash of the lane and fragment index
+__global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int iters, float* __restrict__ sink) {
+  const uint32_t gid = blockIdx.x * 512u + threadIdx.x;
+  s16x8_t fa[2][4], fb[2][2];
+  auto fill = [&](s16x8_t& f, uint32_t salt) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint32_t h = (gid * 0x9E3779B9u) ^ (salt * 0x85EBCA6Bu) ^ ((uint32_t)e * 0xC2B2AE35u);
+      h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 12; h *= 0x297A2D39u; h ^= h >> 15;
+      // sign and 7 mantissa bits from the hash, exponent of 0.5 .. 2
+      const uint32_t bits = (h & 0x8000u) | ((126u + ((h >> 16) % 2u)) << 7) | (h & 0x7Fu);
+      f[e] = pattern ? (short)bits : (short)0;
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fill(fa[s][i], 16u * s + i);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) fill(fb[s][j], 16u * s + 8u + j);
+  }
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT_BF16>(fb[s][j], fa[s][i], acc[i][j]);
+  }
+  float t = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) t += acc[i][j][e];
+  if (t == 12345.678f) sink[0] = t;   // keeps the loop alive; never true for these operands
+}
+
+}  // namespace flashdp
