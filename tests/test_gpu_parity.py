@@ -470,3 +470,17 @@ def test_medium_shapes_default_kernel_choice(shape, schedule):
     X, dY = W.make_layer(w, 0)
     e = check_case(X, dY, 1.0, 1.0, 23, 1, "bf16", schedule)
     print(shape, schedule, e)
+
+
+@pytest.mark.timeout(200)
+def test_fp16_inputs_on_a_llama_sized_layer():
+    # fp16 operands at Llama-7B q_proj width (the default kernel choice is the direct-to-LDS kernel), T shortened so
+    # that the fp64 oracle takes seconds; values as in the workloads (X ~ N(0,1), dY ~ 1e-2 N(0,1) x per-sample scale)
+    rng = np.random.default_rng(99)
+    B, T, P, D = 4, 256, 4096, 4096
+    X = rng.standard_normal((B, T, P)).astype(np.float16)
+    dY = (rng.standard_normal((B, T, D)) * 1e-2 * (10.0 ** rng.uniform(-1, 1, size=(B, 1, 1)))).astype(np.float16)
+    want = O.linear_dp_grad(X.astype(np.float32), dY.astype(np.float32), 1.0, 0.0, 31, 2)
+    for schedule in ("auto", "twopass"):
+        e = check_case(X, dY, 1.0, 1.0, 31, 2, "f16", schedule, oracle=want)
+        print("f16 4096x4096", schedule, e)
