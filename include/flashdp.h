@@ -38,7 +38,8 @@
  *   - Pointers must be 16-byte aligned.  Any positive B, T, d_in, d_out is accepted; the
  *     matrix-core path needs d_in and d_out to be multiples of 8 (16-bit types), other shapes
  *     take a slower generic kernel.
- *   - NaN/Inf in the inputs propagate to out_norms / out_grad.
+ *   - NaN/Inf in the inputs propagate to out_norms / out_grad: a sample with a NaN norm gets a NaN clip
+ *     factor and so turns the whole of out_grad into NaN (it is never let through unclipped).
  *   - Return value: FLASHDP_OK (0) or a negative flashdp_status; on error nothing is enqueued.
  *
  * Environment overrides, read at every call (measurement aids, not needed in normal use):

@@ -29,7 +29,8 @@ __global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restri
   if (tid == 0) {
     const double n = sqrt(red[0]);
     const double ratio = n / (double)C;
-    factors[i] = (float)(1.0 / (ratio > 1.0 ? ratio : 1.0));
+    // written so that a NaN norm gives a NaN factor: a sample whose norm is unknown must not pass unclipped
+    factors[i] = (float)(1.0 / (ratio <= 1.0 ? 1.0 : ratio));
     if (out_norms) out_norms[i] = (float)n;
   }
 }

@@ -484,3 +484,21 @@ def test_fp16_inputs_on_a_llama_sized_layer():
     for schedule in ("auto", "twopass"):
         e = check_case(X, dY, 1.0, 1.0, 31, 2, "f16", schedule, oracle=want)
         print("f16 4096x4096", schedule, e)
+
+
+@pytest.mark.parametrize("schedule", ["scratch", "twopass", "explicit", "ghost"])
+def test_nan_in_one_sample_poisons_the_output_instead_of_passing_unclipped(schedule):
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=3, T=40, dims=[(264, 136)])
+    X, dY = W.make_layer(w, 0)
+    X = X.copy()
+    X[1, 7, 19] = 0x7FC0                      # bfloat16 quiet NaN in sample 1
+    # the paper's formula says nothing about a NaN norm (and max(1, NaN) is whatever the language makes of it); the
+    # library's documented choice is the safe one for privacy: the factor is NaN and the whole output with it.
+    # The other samples' norms are still the oracle's.
+    _, wn = O.linear_dp_grad(X, dY, 1.0, 0.0, 1, 0)
+    assert np.isnan(wn[1])
+    got, gn, _ = run_layer(X, dY, 1.0, 0.0, 1, 0, schedule)
+    assert np.isnan(gn[1]) and np.all(np.isfinite(gn[[0, 2]]))
+    assert np.allclose(gn[[0, 2]], wn[[0, 2]], rtol=1e-4)
+    assert np.all(np.isnan(got))
