@@ -154,19 +154,32 @@ WsLayout ws_layout(const Plan& p, int64_t B, int64_t T, int64_t P, int64_t D, in
   return w;
 }
 
-template <typename Cfg, int MODE, int DT>
-hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
-  static bool attr_set = false;   // one attribute call per instantiation (idempotent, race-benign)
-  auto kern = gemm_mfma_kernel<Cfg, MODE, DT>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
+// Launches one of the tiled matrix-core kernels: raises its dynamic-LDS limit once, grid = tiles (x samples for the
+// per-sample modes).
+template <typename Cfg>
+hipError_t launch_tiled(void (*kern)(GemmArgs), int mode, const GemmArgs& a, hipStream_t st) {
+  static std::mutex m;
+  static std::map<std::pair<int, const void*>, bool> attr_set;   // per device and kernel instantiation
+  {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(m);
+    bool& done = attr_set[std::make_pair(dev, reinterpret_cast<const void*>(kern))];
+    if (!done) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+      if (e != hipSuccess) return e;
+      done = true;
+    }
   }
   const int tiles = a.tiles_m * a.tiles_n;
-  const int grid = (MODE == MODE_ACCUM) ? tiles : tiles * a.B;
+  const int grid = (mode == MODE_ACCUM) ? tiles : tiles * a.B;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, a);
   return hipGetLastError();
+}
+
+template <typename Cfg, int MODE, int DT>
+hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
+  return launch_tiled<Cfg>(gemm_mfma_kernel<Cfg, MODE, DT>, MODE, a, st);
 }
 
 template <int MODE, int DT>
@@ -178,18 +191,7 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& args, hipStream_t st) {
       case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
       case PATH_256x8k32: return launch_mfma<Cfg256x8k32, MODE, DT>(a, st);
-      case PATH_DMA: {
-        static bool attr_set = false;
-        auto kern = gemm_mfma_dma_kernel<CfgDma, MODE, DT>;
-        if (!attr_set) {
-          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, CfgDma::LDS_BYTES);
-          if (e != hipSuccess) return e;
-          attr_set = true;
-        }
-        const int tiles_d = a.tiles_m * a.tiles_n;
-        hipLaunchKernelGGL(kern, dim3(MODE == MODE_ACCUM ? tiles_d : tiles_d * a.B), dim3(CfgDma::NT), CfgDma::LDS_BYTES, st, a);
-        return hipGetLastError();
-      }
+      case PATH_DMA: return launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE, DT>, MODE, a, st);
       default: break;
     }
   }
