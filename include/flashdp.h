@@ -123,9 +123,10 @@ int flashdp_linear_dp_grad(const void* X, const void* dY, int64_t B, int64_t T, 
 
 /* Per-block multi-layer variant: Algorithm 1 for each of n_layers layers (same B and T), enqueued in
  * order on `stream` (a hipStream_t, may be NULL).  `workspace` is caller-owned device memory of at least
- * flashdp_workspace_bytes(...) bytes, reused layer after layer; with workspace == NULL and
- * schedule == TWOPASS or AUTO the library-owned workspace is used as above.  Calls that share a
- * workspace must be ordered on one stream. */
+ * flashdp_workspace_bytes(...) bytes, reused layer after layer; with workspace == NULL the library-owned
+ * workspace is used as above (sized for the schedule asked for).  Calls that share a workspace must be
+ * ordered on one stream; the library-owned workspace is one per device, so this holds for all calls on a
+ * device that pass no workspace of their own, from whichever thread they come. */
 int flashdp_block_dp_grad(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
                           int schedule, void* workspace, size_t workspace_bytes, void* stream);
 
