@@ -187,7 +187,7 @@ int flashdp_set_stages(int mask);
 /* Frees the library-owned workspaces, side streams and events (synchronises the device first). */
 int flashdp_release(void);
 
-/* Name of the schedule the last call on this thread used: "twopass", "scratch", "overlap" or "explicit" ("none" before any). */
+/* Name of the schedule the last call on this thread used: "twopass", "scratch", "overlap", "explicit" or "ghost" ("none" before any). */
 const char* flashdp_last_schedule(void);
 
 const char* flashdp_status_string(int status);
