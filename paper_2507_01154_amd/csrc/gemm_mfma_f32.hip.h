@@ -124,13 +124,17 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma_f32_kernel(const GemmArgs a)
         __syncthreads();   // tile k+1 is in LDS, and every wave has read the last fragments of tile k
         load_frags(cur ^ 1, 0, fa[nb], fb[nb]);
       }
-      if constexpr (ks == KS / 2 - 1) store_lds(cur ^ 1);
-      if constexpr (ks == KS - 2) load_global();
+      constexpr bool do_store = ks == KS / 2 - 1, do_fetch = ks == KS - 2;
+      if constexpr (do_store) store_lds(cur ^ 1);
+      if constexpr (do_fetch) load_global();
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[cb][j], fa[cb][i], acc[i][j], 0, 0, 0);
+      // keep the fragment reads of the next k-step (and the tile copy) between this k-step's matrix-core
+      // instructions instead of in front of the ones that consume them
+      sched_interleave<0, FM * FN, FM + FN, do_store ? C::CA + C::CB : 0, do_fetch ? C::CA + C::CB : 0>();
     });
     if constexpr (MODE == MODE_ACCUM) {
       // sample boundary: keep acc = sum_{j<=i} (c_j / c_i) G_j (see the 16-bit kernel)
