@@ -112,27 +112,41 @@ __global__ __launch_bounds__(GramCfg::NT, 2) void gram_norm_mfma_kernel(const Gr
     store_lds(0);
     load_global(1);
     __syncthreads();
+    // fragments are double-buffered in registers: the reads of k-step ks + 1 go out before the matrix-core
+    // instructions of k-step ks (the first reads of the next k-tile right after the barrier)
+    constexpr int KS = BK / 16;
+    s16x8_t fa[2][2], fb[2][2];
+    auto load_frags = [&](int stage, int ks, s16x8_t* pfa, s16x8_t* pfb) {
+      const unsigned short* pa = As + stage * GramCfg::STAGE + fr_a + ks * 16;
+      const unsigned short* pb = Bs + stage * GramCfg::STAGE + fr_b + ks * 16;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) pfa[i] = *(const s16x8_t*)(pa + i * 32 * LD);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) pfb[j] = *(const s16x8_t*)(pb + j * 32 * LD);
+    };
+    load_frags(0, 0, fa[0], fb[0]);
     for (int kt = 0; kt < nk; ++kt) {
       const int cur = kt & 1;
-      const unsigned short* pa = As + cur * GramCfg::STAGE + fr_a;
-      const unsigned short* pb = Bs + cur * GramCfg::STAGE + fr_b;
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        s16x8_t fa[2], fb[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) fa[i] = *(const s16x8_t*)(pa + i * 32 * LD + ks * 16);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) fb[j] = *(const s16x8_t*)(pb + j * 32 * LD + ks * 16);
-        if (ks == 0) {
+      static_for<KS>([&](auto ks_c) {
+        constexpr int ks = decltype(ks_c)::value;
+        constexpr int cb = ks & 1, nb = cb ^ 1;
+        constexpr bool copy = ks == 0;
+        if constexpr (ks + 1 < KS) {
+          load_frags(cur, ks + 1, fa[nb], fb[nb]);
+        } else {
+          __syncthreads();   // tile kt + 1 is in LDS and every wave has read the last fragments of tile kt
+          load_frags(cur ^ 1, 0, fa[nb], fb[nb]);
+        }
+        if constexpr (copy) {
           store_lds(cur ^ 1);     // tile kt + 1 (in registers since the last trip) to the other stage
           load_global(kt + 2);
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j) acc[g][i][j] = mfma32<DT>(fa[i], fb[j], acc[g][i][j]);
-      }
-      __syncthreads();
+          for (int j = 0; j < 2; ++j) acc[g][i][j] = mfma32<DT>(fa[cb][i], fb[cb][j], acc[g][i][j]);
+        sched_interleave<0, 4, 4, copy ? 2 * CH : 0, copy ? 2 * CH : 0>();
+      });
     }
   });
 
