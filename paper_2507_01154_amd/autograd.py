@@ -15,6 +15,49 @@ import torch
 from . import binding as F
 
 
+class deferred_weight_grads:
+    """Context manager: DPLinear backward passes inside it only record (X, dY) of their layer; on exit all
+    recorded layers go to the library in ONE flashdp_block_dp_grad call per (B, T, dtype) group, so that the
+    per-block schedule applies (the aggregation of one layer running beside the contraction of the next)
+    instead of one isolated call per layer.  The weights' .grad fields are filled (or added to) on exit.  The
+    price is that X and dY of every recorded layer stay alive until then."""
+
+    _active = None
+
+    def __init__(self, schedule="auto"):
+        self.schedule = schedule
+        self.pending = []
+
+    def __enter__(self):
+        if deferred_weight_grads._active is not None:
+            raise RuntimeError("deferred_weight_grads does not nest")
+        deferred_weight_grads._active = self
+        return self
+
+    def __exit__(self, exc_type, exc, tb):
+        deferred_weight_grads._active = None
+        if exc_type is None:
+            self.flush()
+        self.pending = []
+        return False
+
+    def flush(self):
+        groups = {}
+        for rec in self.pending:
+            groups.setdefault((rec["B"], rec["T"], rec["X"].dtype), []).append(rec)
+        for (B, T, _), recs in groups.items():
+            layers = []
+            for r in recs:
+                r["out"] = torch.empty(r["weight"].shape, dtype=torch.float32, device=r["X"].device)
+                layers.append(dict(X=r["X"], dY=r["dY"], d_in=r["weight"].shape[1], d_out=r["weight"].shape[0], C=r["C"],
+                                   sigma=r["sigma"], seed=r["seed"], layer=r["layer"], out_grad=r["out"], out_norms=r["norms"]))
+            F.flashdp_block_dp_grad(layers, B, T, F.dtype_code(recs[0]["X"]), self.schedule)
+            for r in recs:
+                g = r["out"].to(r["weight"].dtype)
+                r["weight"].grad = g if r["weight"].grad is None else r["weight"].grad + g
+        self.pending = []
+
+
 class _DPLinearFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, weight, C, sigma, seed, layer, schedule, norms_out):
@@ -33,12 +76,17 @@ class _DPLinearFn(torch.autograd.Function):
         T = xs.shape[1]
         if xs.dtype != dys.dtype:
             dys = dys.to(xs.dtype)
-        grad_w = torch.empty((d_out, d_in), dtype=torch.float32, device=x.device)
         norms = norms_out if norms_out is not None else torch.empty((B,), dtype=torch.float32, device=x.device)
+        grad_x = torch.matmul(dy, weight) if ctx.needs_input_grad[0] else None
+        pending = deferred_weight_grads._active
+        if pending is not None:   # hand the layer to the per-block call made when the context exits
+            pending.pending.append(dict(X=xs, dY=dys, B=B, T=T, weight=weight, C=C, sigma=sigma, seed=seed, layer=layer,
+                                        norms=norms))
+            return grad_x, None, None, None, None, None, None, None
+        grad_w = torch.empty((d_out, d_in), dtype=torch.float32, device=x.device)
         L = [dict(X=xs, dY=dys, d_in=d_in, d_out=d_out, C=C, sigma=sigma, seed=seed, layer=layer,
                   out_grad=grad_w, out_norms=norms)]
         F.flashdp_block_dp_grad(L, B, T, F.dtype_code(xs), schedule)
-        grad_x = torch.matmul(dy, weight) if ctx.needs_input_grad[0] else None
         return grad_x, grad_w.to(weight.dtype), None, None, None, None, None, None
 
 

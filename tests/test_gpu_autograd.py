@@ -48,3 +48,39 @@ def test_two_layer_mlp_backward_matches_oracle():
         assert np.any(wn > lin.C) and got.shape == (do, di)
     # the seed folds the step in: another step, another noise
     assert l1.noise_seed() != DPLinear(d0, d1, seed=3, device=DEV).noise_seed()
+
+
+def test_deferred_block_call_gives_the_same_gradients():
+    """Inside deferred_weight_grads the layers of one backward pass go to the library in a single per-block call
+    (overlapped schedule when the shapes allow); the gradients are the ones the layer-by-layer calls produce."""
+    from paper_2507_01154_amd.autograd import DPLinear, deferred_weight_grads
+    import paper_2507_01154_amd as F
+    torch.manual_seed(1)
+    B, T, d0, d1, d2 = 4, 64, 1024, 1536, 1024
+    l1 = DPLinear(d0, d1, C=0.05, sigma=0.5, seed=5, layer=0, device=DEV)
+    l2 = DPLinear(d1, d2, C=0.05, sigma=0.5, seed=5, layer=1, device=DEV)
+    x = torch.randn(B, T, d0, device=DEV).bfloat16()
+    target = torch.randn(B, T, d2, device=DEV).bfloat16()
+
+    def run():
+        l1.weight.grad = l2.weight.grad = None
+        y = l2(torch.relu(l1(x)))
+        (((y.float() - target.float()) ** 2).sum()).backward()
+
+    run()
+    torch.cuda.synchronize()
+    ref = [l1.weight.grad.clone(), l2.weight.grad.clone()]
+    ref_norms = [l1.last_norms.clone(), l2.last_norms.clone()]
+    with deferred_weight_grads():
+        run()
+        assert l1.weight.grad is None and l2.weight.grad is None      # nothing computed yet
+    torch.cuda.synchronize()
+    assert F.flashdp_last_schedule() in ("overlap", "scratch")
+    assert torch.equal(l1.weight.grad, ref[0]) and torch.equal(l2.weight.grad, ref[1])
+    assert torch.equal(l1.last_norms, ref_norms[0]) and torch.equal(l2.last_norms, ref_norms[1])
+    # a second deferred pass without clearing adds to .grad, as autograd would
+    with deferred_weight_grads():
+        y = l2(torch.relu(l1(x)))
+        (((y.float() - target.float()) ** 2).sum()).backward()
+    torch.cuda.synchronize()
+    assert torch.allclose(l1.weight.grad.float(), 2 * ref[0].float(), rtol=2e-2, atol=1e-3)
