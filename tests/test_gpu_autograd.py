@@ -84,3 +84,65 @@ def test_deferred_block_call_gives_the_same_gradients():
         (((y.float() - target.float()) ** 2).sum()).backward()
     torch.cuda.synchronize()
     assert torch.allclose(l1.weight.grad.float(), 2 * ref[0].float(), rtol=2e-2, atol=1e-3)
+
+
+def test_small_decoder_block_trains_with_per_layer_clipping():
+    """The seven linears of a (tiny) Llama-style decoder block as DPLinear, per-layer clipping on each, one
+    per-block library call per step (deferred mode), plain SGD: with sigma = 0 the summed loss goes down, every
+    layer reports per-sample norms, and with the clipping threshold far above the norms the weight gradients are
+    the ordinary ones."""
+    from paper_2507_01154_amd.autograd import DPLinear, deferred_weight_grads
+    torch.manual_seed(2)
+    B, T, d, h, ff = 4, 32, 128, 4, 256
+
+    def make(C):
+        names = [("q", d, d), ("k", d, d), ("v", d, d), ("o", d, d), ("gate", d, ff), ("up", d, ff), ("down", ff, d)]
+        return {n: DPLinear(i, o, C=C, sigma=0.0, seed=11, layer=k, device=DEV) for k, (n, i, o) in enumerate(names)}
+
+    def block(L, x):
+        def norm(t):
+            return (t.float() * torch.rsqrt(t.float().pow(2).mean(-1, keepdim=True) + 1e-6)).to(t.dtype)
+        xn = norm(x)
+        q, k, v = (L[n](xn).view(B, T, h, d // h).transpose(1, 2) for n in ("q", "k", "v"))
+        a = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B, T, d)
+        x = x + L["o"](a)
+        xn = norm(x)
+        return x + L["down"](torch.nn.functional.silu(L["gate"](xn)) * L["up"](xn))
+
+    x = torch.randn(B, T, d, device=DEV).bfloat16()
+    target = torch.randn(B, T, d, device=DEV).bfloat16()
+
+    # (1) clipping threshold far above every norm: DP gradients = ordinary gradients of the summed loss
+    L = make(C=1e6)
+    ref = {n: m.weight.detach().clone().float().requires_grad_(True) for n, m in L.items()}
+
+    class Plain:   # the same block on plain fp32 copies of the weights
+        def __init__(self, w): self.w = w
+        def __call__(self, t): return (t.float() @ self.w.t()).to(t.dtype)
+    loss_ref = ((block({n: Plain(w) for n, w in ref.items()}, x).float() - target.float()) ** 2).sum()
+    loss_ref.backward()
+    with deferred_weight_grads():
+        ((block(L, x).float() - target.float()) ** 2).sum().backward()
+    torch.cuda.synchronize()
+    for n, m in L.items():
+        got, want = m.weight.grad.float(), ref[n].grad
+        assert torch.linalg.norm(got - want) / torch.linalg.norm(want) < 3e-2, n     # bf16 activations and grads
+        assert m.last_norms.shape == (B,) and bool(torch.all(m.last_norms > 0))
+
+    # (2) a realistic threshold: every sample clips on every layer, and SGD on the clipped sums still learns
+    L = make(C=1.0)
+    losses = []
+    for step in range(25):
+        for m in L.values():
+            m.weight.grad = None
+            m.step = step
+        with deferred_weight_grads():
+            loss = ((block(L, x).float() - target.float()) ** 2).sum()
+            loss.backward()
+        losses.append(float(loss.detach()))
+        with torch.no_grad():
+            for m in L.values():
+                m.weight -= (0.05 / B) * m.weight.grad
+    torch.cuda.synchronize()
+    assert all(bool(torch.all(m.last_norms > m.C)) for m in L.values())              # the DP regime: all clipped
+    assert losses[-1] < 0.9 * losses[0], losses
