@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (average over the launches of one step), scaled by what the same counters read for a 1 GiB copy
-# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Source: profiles/gemm_mfma_spill__llama13b_block.md.
+# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Source: the rocprofv3 summary of that kernel under profiles/.
 MEASURED_TRAFFIC = {
     ("llama13b_block", "scratch"): {"read_bytes": 2.29e9, "write_bytes": 0.725e9},
 }
