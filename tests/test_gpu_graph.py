@@ -31,7 +31,7 @@ def test_graph_capture_and_replay(schedule, case):
         layers = _layers(w, [0])
     else:
         base = W.WORKLOADS["llama13b_block"]
-        # large enough for the 256x256 path (>= 1024 work items per layer), which the overlapped schedule needs
+        # large enough for the 256x256 path (many 256 x 256 work items per layer), which the overlapped schedule needs
         w = W.scaled_down(base, B=8, T=128, dims=[(2048, 4096), (4096, 2048), (2048, 4096)])
         layers = _layers(w, [0, 1, 2])
     arr = F.make_layers(layers)
