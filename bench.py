@@ -101,13 +101,14 @@ def time_each(fn, steps, warmup):
 
 
 def mfma_only(F, torch, dev):
-    """The matrix cores alone (register-resident operands, the contraction kernel's instruction mix, no memory):
-    what this part sustains on all-zero and on random operands, in TFLOP/s.  ~0.1 s of GPU time each."""
+    """The matrix cores alone (register-resident operands, the contraction kernel's instruction mix, no memory),
+    and with the operand fragments re-read from LDS as the kernel does (lds_*): what this part sustains on all-zero
+    and on random operands, in TFLOP/s.  ~0.1 s of GPU time each."""
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
     wgs, iters = 1024, 20000
     flop = wgs * 8 * iters * 16 * 32768.0
     out = {}
-    for name, pattern in (("zeros", 0), ("random", 1)):
+    for name, pattern in (("zeros", 0), ("random", 1), ("lds_zeros", 2), ("lds_random", 3)):
         ms = time_events(lambda: F.flashdp_mfma_probe(pattern, iters, wgs, sink), 3, 2)
         out[name + "_tflops"] = round(flop / ms / 1e9, 1)
     return out

@@ -172,8 +172,10 @@ int flashdp_set_schedule(int schedule);
 /* Measurement aid, not a step of the method: runs the matrix-core instruction mix of the contraction kernel's
  * inner loop (bf16, 32x32x16, eight accumulators per wave) on register-resident operands - no memory, no LDS,
  * no barrier - so that a benchmark can quote the rate this part actually sustains next to the nominal peak.
- * pattern 0 = all-zero operands, 1 = pseudo-random operands; `workgroups` workgroups of 8 waves, each wave
- * issuing 16 * iters instructions of 32768 FLOP; sink (device, 4 bytes) is never written in practice.
+ * pattern 0 = all-zero operands, 1 = pseudo-random operands, both held in registers; 2 and 3 = the same two
+ * with the operand fragments re-read from LDS every k-step through the contraction kernel's transposed reads
+ * (matrix cores + LDS traffic, still no memory loads and no barrier).  `workgroups` workgroups of 8 waves, each
+ * wave issuing 16 * iters instructions of 32768 FLOP; sink (device, 4 bytes) is never written in practice.
  * INVALID_ARGUMENT for other patterns, iters or workgroups <= 0 or absurdly large, or a null sink. */
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream);
 

@@ -157,7 +157,7 @@ WsLayout ws_layout(const Plan& p, int64_t B, int64_t T, int64_t P, int64_t D, in
 // Launches one of the tiled matrix-core kernels: raises its dynamic-LDS limit once, grid = tiles (x samples for the
 // per-sample modes).
 template <typename Cfg>
-hipError_t launch_tiled(void (*kern)(GemmArgs), int mode, const GemmArgs& a, hipStream_t st) {
+hipError_t launch_tiled(void (*kern)(GemmArgs), int mode, const GemmArgs& a, hipStream_t st, bool lockstep = false) {
   static std::mutex m;
   static std::map<std::pair<int, const void*>, bool> attr_set;   // per device and kernel instantiation
   {
@@ -172,8 +172,10 @@ hipError_t launch_tiled(void (*kern)(GemmArgs), int mode, const GemmArgs& a, hip
     }
   }
   const int tiles = a.tiles_m * a.tiles_n;
-  const int grid = (mode == MODE_ACCUM) ? tiles : tiles * a.B;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, a);
+  // lockstep: the per-sample grid of the direct-to-LDS kernel, padded so that every XCD has the same number of slots
+  const int64_t grid = (mode == MODE_ACCUM) ? tiles : lockstep ? (int64_t)8 * ((tiles + 7) / 8) * a.B : (int64_t)tiles * a.B;
+  if (grid >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, a);
   return hipGetLastError();
 }
 
@@ -191,7 +193,7 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& args, hipStream_t st) {
       case PATH_256x8: return launch_mfma<Cfg256x8, MODE, DT>(a, st);
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
       case PATH_256x8k32: return launch_mfma<Cfg256x8k32, MODE, DT>(a, st);
-      case PATH_DMA: return launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE, DT>, MODE, a, st);
+      case PATH_DMA: return launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE, DT>, MODE, a, st, /*lockstep=*/true);
       default: break;
     }
   }
@@ -597,12 +599,16 @@ int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* 
 }
 
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream) {
-  if ((pattern != 0 && pattern != 1) || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
+  if (pattern < 0 || pattern > 3 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
     return FLASHDP_INVALID_ARGUMENT;
   int dev = 0;
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), pattern, iters, sink);
+  if (pattern >= 2) {   // 2, 3: zeros / random with the operand fragments re-read from LDS every k-step
+    hipLaunchKernelGGL(mfma_lds_probe_kernel, dim3((unsigned)workgroups), dim3(512), lds_plan::STAGE_ELEMS * 2, static_cast<hipStream_t>(stream), pattern - 2, iters, sink);
+  } else {
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), pattern, iters, sink);
+  }
   HIP_TRY(hipGetLastError());
   return FLASHDP_OK;
 }

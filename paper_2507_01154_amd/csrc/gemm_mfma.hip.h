@@ -149,6 +149,24 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
+// Per-sample passes: all eight XCDs work on the SAME sample at the same time, each on its own eighth of the
+// tiles, and move on to the next sample together.  The operands of one sample (tens of MB) then stay in the
+// memory-side cache shared by the XCDs while all of its tiles are computed; with each XCD on a sample of its own
+// the eight working sets together exceed that cache and L2 misses go to HBM.
+// Workgroup ids congruent mod 8 share an XCD; XCD x owns tiles [off_x, off_x + n_x) of every sample, n_x =
+// tiles / 8 (+ 1 for the first tiles % 8 XCDs).  The grid is 8 * ceil(tiles / 8) * B workgroups; a workgroup
+// whose slot lies beyond its XCD's share returns false and exits at once.
+__device__ __forceinline__ bool lockstep_item(int bid, int tiles, int* sample, int* tile) {
+  const int per = tiles >> 3, rem = tiles & 7, slots = (tiles + 7) >> 3;
+  const int xcd = bid & 7, idx = bid >> 3;
+  const int n_x = per + (xcd < rem ? 1 : 0);
+  const int off_x = xcd * per + (xcd < rem ? xcd : rem);
+  const int s = idx / slots, t = idx - s * slots;
+  *sample = s;
+  *tile = off_x + t;
+  return t < n_x;
+}
+
 // Tiles are walked in bands of GROUP_M tile rows, column by column inside a band, so that consecutive
 // work items reuse the same dY panel (rows) and neighbouring X panels.
 template <int GROUP_M>

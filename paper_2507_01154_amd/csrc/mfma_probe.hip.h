@@ -9,6 +9,7 @@
 #include <stdint.h>
 
 #include "gemm_mfma.hip.h"
+#include "lds_plan.h"
 
 namespace flashdp {
 
@@ -56,6 +57,70 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
 #pragma unroll
       for (int e = 0; e < 16; ++e) t += acc[i][j][e];
   if (t == 12345.678f) sink[0] = t;   // keeps the loop alive; never true for these operands
+}
+
+// The same instruction mix with the operand fragments coming from LDS through the transposed reads of the
+// contraction kernel (a 32 KB stage filled once with zeros or pseudo-random values, re-read every k-tile):
+// matrix cores + LDS traffic, still no memory loads and no barrier in the loop.
+__global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int iters, float* __restrict__ sink) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % 2, wave_n = wave / 2;
+  for (int e = tid; e < lds_plan::STAGE_ELEMS; e += 512) {
+    uint32_t h = ((uint32_t)e * 0x9E3779B9u) ^ (blockIdx.x * 0x85EBCA6Bu);
+    h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 12; h *= 0x297A2D39u; h ^= h >> 15;
+    const uint32_t bits = (h & 0x8000u) | ((126u + ((h >> 16) % 2u)) << 7) | (h & 0x7Fu);
+    lds[e] = pattern ? (unsigned short)bits : (unsigned short)0;
+  }
+  __syncthreads();
+  int a_rd[4], b_rd[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_rd[i] = lds_plan::frag_offset(lane, wave_m * 4 + i);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) b_rd[j] = lds_plan::OPERAND_ELEMS + lds_plan::frag_offset(lane, wave_n * 2 + j);
+  s16x8_t fa[2][4], fb[2][2];
+  auto load_frags = [&](int ks, s16x8_t* pfa, s16x8_t* pfb) {
+    const unsigned short* base = lds + ks * 16 * lds_plan::ROW;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const s16x4_t lo = lds_read_tr(base + a_rd[i]);
+      const s16x4_t hi = lds_read_tr(base + a_rd[i] + 4 * lds_plan::ROW);
+      pfa[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const s16x4_t lo = lds_read_tr(base + b_rd[j]);
+      const s16x4_t hi = lds_read_tr(base + b_rd[j] + 4 * lds_plan::ROW);
+      pfb[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  load_frags(0, fa[0], fb[0]);
+  for (int it = 0; it < iters; ++it) {
+    static_for<2>([&](auto ks_c) {
+      constexpr int ks = decltype(ks_c)::value;
+      load_frags(ks ^ 1, fa[ks ^ 1], fb[ks ^ 1]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT_BF16>(fb[ks][j], fa[ks][i], acc[i][j]);
+      sched_interleave<0, 8, 12, 0, 0>();
+    });
+  }
+  float t = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) t += acc[i][j][e];
+  if (t == 12345.678f) sink[0] = t;
 }
 
 }  // namespace flashdp
