@@ -200,17 +200,7 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& args, hipStream_t st) {
   const int tiles = a.tiles_m * a.tiles_n;
   const int grid = (MODE == MODE_ACCUM) ? tiles : tiles * a.B;
   if constexpr (DT == DT_F32) {
-    if (p.path == PATH_F32) {
-      static bool attr_set = false;
-      auto kern = gemm_mfma_f32_kernel<MODE>;
-      if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, F32Cfg::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-      }
-      hipLaunchKernelGGL(kern, dim3(grid), dim3(F32Cfg::NT), F32Cfg::LDS_BYTES, st, a);
-      return hipGetLastError();
-    }
+    if (p.path == PATH_F32) return launch_tiled<F32Cfg>(gemm_mfma_f32_kernel<MODE>, MODE, a, st, /*lockstep=*/true);
   }
   hipLaunchKernelGGL((gemm_simple_kernel<MODE, DT>), dim3(grid), dim3(256), 0, st, a);
   return hipGetLastError();

@@ -39,11 +39,13 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma_f32_kernel(const GemmArgs a)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave % C::WAVES_M, wave_n = wave / C::WAVES_M;
   const int tiles = a.tiles_m * a.tiles_n;
-  const int total = (MODE == MODE_ACCUM) ? tiles : tiles * a.B;
-  const int item = xcd_remap(blockIdx.x, total);
-  const int sample0 = (MODE == MODE_ACCUM) ? 0 : item / tiles;
+  int sample0 = 0, tile;
+  if constexpr (MODE == MODE_ACCUM) {
+    tile = xcd_remap(blockIdx.x, tiles);
+  } else {
+    if (!lockstep_item(blockIdx.x, tiles, &sample0, &tile)) return;   // the whole workgroup, before any barrier
+  }
   const int n_samples = (MODE == MODE_ACCUM) ? a.B : 1;
-  const int tile = (MODE == MODE_ACCUM) ? item : item - sample0 * tiles;
   int tm, tn;
   tile_coords<8>(tile, a.tiles_m, a.tiles_n, &tm, &tn);
   const int m0 = tm * C::BM, n0 = tn * C::BN;
