@@ -172,8 +172,8 @@ hipError_t launch_tiled(void (*kern)(GemmArgs), int mode, const GemmArgs& a, hip
     }
   }
   const int tiles = a.tiles_m * a.tiles_n;
-  // lockstep: the per-sample grid of the direct-to-LDS kernel, padded so that every XCD has the same number of slots
-  const int64_t grid = (mode == MODE_ACCUM) ? tiles : lockstep ? (int64_t)8 * ((tiles + 7) / 8) * a.B : (int64_t)tiles * a.B;
+  // lockstep: the per-sample grid in blocks of 32 tiles dealt to the XCDs in turn (see shared_block_item)
+  const int64_t grid = (mode == MODE_ACCUM) ? tiles : lockstep ? shared_block_grid(tiles, a.B) : (int64_t)tiles * a.B;
   if (grid >= (int64_t(1) << 31)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, a);
   return hipGetLastError();

@@ -149,22 +149,28 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
-// Per-sample passes: all eight XCDs work on the SAME sample at the same time, each on its own eighth of the
-// tiles, and move on to the next sample together.  The operands of one sample (tens of MB) then stay in the
-// memory-side cache shared by the XCDs while all of its tiles are computed; with each XCD on a sample of its own
-// the eight working sets together exceed that cache and L2 misses go to HBM.
-// Workgroup ids congruent mod 8 share an XCD; XCD x owns tiles [off_x, off_x + n_x) of every sample, n_x =
-// tiles / 8 (+ 1 for the first tiles % 8 XCDs).  The grid is 8 * ceil(tiles / 8) * B workgroups; a workgroup
-// whose slot lies beyond its XCD's share returns false and exits at once.
-__device__ __forceinline__ bool lockstep_item(int bid, int tiles, int* sample, int* tile) {
-  const int per = tiles >> 3, rem = tiles & 7, slots = (tiles + 7) >> 3;
+// Per-sample passes: work is handed out in blocks of 32 consecutive tiles of one sample (in the band order
+// of tile_coords below that is 8 tile rows x 4 tile columns: 12 operand panels for 32 tiles), block q to XCD
+// q % 8.  Workgroup ids congruent mod 8 share an XCD, so the 32 workgroups resident on an XCD are one such
+// block and share its panels in that XCD's L2, and the eight XCDs work on eight consecutive blocks - almost
+// always of the same sample - at the same time: one sample's operands (tens of MB) stay in the memory-side
+// cache shared by the XCDs for as long as they are needed.  (One sample per XCD made eight working sets compete
+// for that cache; an eighth of every sample per XCD cut the blocks of 32 into pieces.)
+// The grid is 8 * ceil(B * blocks / 8) * 32 workgroups; those beyond the last tile of a block, or beyond the
+// last block, return false and exit at once.
+constexpr int SHARE_BLOCK = 32;
+__host__ __device__ __forceinline__ int64_t shared_block_grid(int tiles, int B) {
+  const int64_t blocks = (tiles + SHARE_BLOCK - 1) / SHARE_BLOCK;
+  return 8 * ((B * blocks + 7) / 8) * SHARE_BLOCK;
+}
+__device__ __forceinline__ bool shared_block_item(int bid, int tiles, int B, int* sample, int* tile) {
+  const int blocks = (tiles + SHARE_BLOCK - 1) / SHARE_BLOCK;
   const int xcd = bid & 7, idx = bid >> 3;
-  const int n_x = per + (xcd < rem ? 1 : 0);
-  const int off_x = xcd * per + (xcd < rem ? xcd : rem);
-  const int s = idx / slots, t = idx - s * slots;
+  const int q = 8 * (idx / SHARE_BLOCK) + xcd, w = idx % SHARE_BLOCK;
+  const int s = q / blocks, t = (q - s * blocks) * SHARE_BLOCK + w;
   *sample = s;
-  *tile = off_x + t;
-  return t < n_x;
+  *tile = t;
+  return s < B && t < tiles;
 }
 
 // Tiles are walked in bands of GROUP_M tile rows, column by column inside a band, so that consecutive

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kern
   if constexpr (MODE == MODE_ACCUM) {
     tile = xcd_remap(blockIdx.x, tiles);
   } else {
-    if (!lockstep_item(blockIdx.x, tiles, &sample0, &tile)) return;   // the whole workgroup, before any barrier
+    if (!shared_block_item(blockIdx.x, tiles, a.B, &sample0, &tile)) return;   // the whole workgroup, before any barrier
   }
   const int n_samples = (MODE == MODE_ACCUM) ? a.B : 1;
   int tm, tn;

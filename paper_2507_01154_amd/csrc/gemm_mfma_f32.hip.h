@@ -43,7 +43,7 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma_f32_kernel(const GemmArgs a)
   if constexpr (MODE == MODE_ACCUM) {
     tile = xcd_remap(blockIdx.x, tiles);
   } else {
-    if (!lockstep_item(blockIdx.x, tiles, &sample0, &tile)) return;   // the whole workgroup, before any barrier
+    if (!shared_block_item(blockIdx.x, tiles, a.B, &sample0, &tile)) return;   // the whole workgroup, before any barrier
   }
   const int n_samples = (MODE == MODE_ACCUM) ? a.B : 1;
   int tm, tn;
