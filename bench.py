@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # script (average over the launches of one step), scaled by what the same counters read for a 1 GiB copy
 # (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Source: the rocprofv3 summary of that kernel under profiles/.
 MEASURED_TRAFFIC = {
-    ("llama13b_block", "scratch"): {"read_bytes": 3.79e9, "write_bytes": 0.725e9},
+    ("llama13b_block", "scratch"): {"read_bytes": 2.78e9, "write_bytes": 0.725e9},
 }
 
 
