@@ -142,6 +142,25 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
                                 int schedule, void* workspace, size_t workspace_bytes, void* stream,
                                 int accumulate, int add_noise);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  flashdp_block_dp_grad for ONE layer under the SCRATCH schedule (same kernels, same
+ * arithmetic, bit-identical results), with the schedule's workspace - clip factors, per-workgroup norm partials and
+ * the parked per-sample tiles - kept in a fixed array of flashdp_static_scratch_bytes() (64 MiB) of device memory
+ * that is part of the library's code object: each GPU the library runs on holds that array from the first use of
+ * the library on it until the process ends.  The call allocates and frees nothing (no hipMalloc / hipFree, no
+ * library-owned workspace, no side stream); the caller passes inputs and outputs as usual, dtype and layer as
+ * arguments instead of thread context, and `stream` (a hipStream_t, may be NULL) to enqueue on.
+ * Limit: flashdp_workspace_bytes(layer, 1, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH) must not exceed
+ * flashdp_static_scratch_bytes(), i.e. roughly B * d_out * d_in * (2 or, for fp32 inputs, 4) bytes <= 64 MiB
+ * (the GPT-2 up-projection at B = 8 takes 36 MiB); larger problems return FLASHDP_WORKSPACE_TOO_SMALL with nothing
+ * enqueued.  All calls on one GPU share that GPU's array: calls that can overlap in time on one GPU (different
+ * streams, different threads) race on it and must be ordered by the caller.  The array keeps the last call's
+ * contents; nothing in it needs clearing between calls, because a call reads only what it has itself written. */
+int flashdp_linear_dp_grad_static(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                  int dtype, float C, float sigma, uint64_t seed, uint32_t layer, float* out_grad,
+                                  float* out_norms, void* stream);
+size_t flashdp_static_scratch_bytes(void);
+
 /* Bytes of workspace the given schedule needs for these layers (the maximum over layers).  Returns 0 on
  * invalid arguments. */
 size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,

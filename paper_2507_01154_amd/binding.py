@@ -60,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.flashdp_block_dp_grad_micro.restype = ci
         L.flashdp_workspace_bytes.argtypes = [lp, ci, i64, i64, ci, ci]
         L.flashdp_workspace_bytes.restype = sz
+        L.flashdp_linear_dp_grad_static.argtypes = [vp, vp, i64, i64, i64, i64, ci, f32, f32, u64, u32, vp, vp, vp]
+        L.flashdp_linear_dp_grad_static.restype = ci
+        L.flashdp_static_scratch_bytes.argtypes = []
+        L.flashdp_static_scratch_bytes.restype = sz
         L.flashdp_plain_grad.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, vp]
         L.flashdp_plain_grad.restype = ci
         L.flashdp_noise_field.argtypes = [u64, u32, i64, vp, vp]
@@ -208,6 +212,18 @@ def flashdp_block_dp_grad_micro(layers, B: int, T: int, dtype: int, schedule=SCH
     _check(lib().flashdp_block_dp_grad_micro(arr, len(arr), B, T, int(dtype), schedule_code(schedule), ws_ptr, ws_bytes,
                                              _stream_handle(stream), int(bool(accumulate)), int(bool(add_noise))),
            "flashdp_block_dp_grad_micro")
+
+
+def flashdp_linear_dp_grad_static(X, dY, B: int, T: int, d_in: int, d_out: int, dtype: int, C: float, sigma: float,
+                                  seed: int, layer: int, out_grad, out_norms=None, stream=None):
+    """The entry point that allocates nothing: one layer, scratch schedule, workspace in the library's static array."""
+    _check(lib().flashdp_linear_dp_grad_static(_ptr(X), _ptr(dY), B, T, d_in, d_out, int(dtype), C, sigma, seed, layer,
+                                               _ptr(out_grad), _ptr(out_norms), _stream_handle(stream)),
+           "flashdp_linear_dp_grad_static")
+
+
+def flashdp_static_scratch_bytes() -> int:
+    return int(lib().flashdp_static_scratch_bytes())
 
 
 def flashdp_plain_grad(X, dY, B: int, T: int, d_in: int, d_out: int, dtype: int, out_grad, stream=None):

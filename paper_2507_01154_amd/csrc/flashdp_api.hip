@@ -23,6 +23,14 @@
 
 using namespace flashdp;
 
+// Working memory of flashdp_linear_dp_grad_static: the per-layer workspace of the scratch schedule (clip
+// factors, per-workgroup norm partials, the parked per-sample tiles) in device memory that comes with the
+// code object, so that the entry point never allocates.  Every device the library is loaded on holds its own
+// copy at its own address until the process ends.  In host code the name below only stands for the symbol:
+// the address kernels are given comes from hipGetSymbolAddress, once per device (static_scratch_ptr).
+#define FLASHDP_STATIC_SCRATCH_BYTES (size_t(64) << 20)
+static __device__ __align__(256) unsigned char scratch[FLASHDP_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 struct Context {
@@ -48,6 +56,22 @@ struct SideStream {
 };
 std::map<int, SideStream> g_side;
 std::mutex g_side_mutex;
+
+std::mutex g_static_mutex;
+std::map<int, void*> g_static_ptr;   // device -> address of that device's copy of `scratch`
+
+// Device address of the current device's copy of the static scratch (looked up once per device).
+int static_scratch_ptr(int dev, char** ptr) {
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  auto it = g_static_ptr.find(dev);
+  if (it == g_static_ptr.end()) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; }
+    it = g_static_ptr.emplace(dev, p).first;
+  }
+  *ptr = static_cast<char*>(it->second);
+  return FLASHDP_OK;
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -533,6 +557,31 @@ int flashdp_linear_dp_grad(const void* X, const void* dY, int64_t B, int64_t T, 
   L.X = X; L.dY = dY; L.d_in = d_in; L.d_out = d_out; L.C = C; L.sigma = sigma; L.seed = seed;
   L.layer = g_ctx.layer; L.out_grad = out_grad; L.out_norms = out_norms;
   return flashdp_block_dp_grad(&L, 1, B, T, g_ctx.dtype, g_ctx.schedule, g_ctx.ws, g_ctx.ws_bytes, g_ctx.stream);
+}
+
+size_t flashdp_static_scratch_bytes(void) { return FLASHDP_STATIC_SCRATCH_BYTES; }
+
+int flashdp_linear_dp_grad_static(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                  int dtype, float C, float sigma, uint64_t seed, uint32_t layer, float* out_grad,
+                                  float* out_norms, void* stream) {
+  if (!valid_dtype(dtype)) return FLASHDP_INVALID_ARGUMENT;
+  flashdp_layer_t L;
+  L.X = X; L.dY = dY; L.d_in = d_in; L.d_out = d_out; L.C = C; L.sigma = sigma; L.seed = seed;
+  L.layer = layer; L.out_grad = out_grad; L.out_norms = out_norms;
+  int st = check_layer(L, B, T);
+  if (st != FLASHDP_OK) return st;
+  if (layer_ws_bytes(L, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH) > FLASHDP_STATIC_SCRATCH_BYTES) return FLASHDP_WORKSPACE_TOO_SMALL;
+  int dev = 0;
+  st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  char* ws = nullptr;
+  st = static_scratch_ptr(dev, &ws);
+  if (st != FLASHDP_OK) return st;
+  // Every part of the workspace a call reads it has written itself first (partials by the contraction, factors
+  // by the clip kernel, the parked tiles by the spill), so nothing has to be cleared between calls.
+  st = run_layer(L, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, ws, static_cast<hipStream_t>(stream), false, true);
+  if (st == FLASHDP_OK) g_ctx.last_schedule = "scratch";
+  return st;
 }
 
 size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype, int schedule) {
