@@ -19,15 +19,27 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# MI355X dense MFMA peaks by input type (TFLOP/s); bf16 and fp16 share one figure
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "fp32": 157.3}
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script (average over the launches of one step), scaled by what the same counters read for a 1 GiB copy
-# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Source: the rocprofv3 summary of that kernel under profiles/.
-MEASURED_TRAFFIC = {
-    ("llama13b_block", "scratch"): {"read_bytes": 2.78e9, "write_bytes": 0.725e9},
-}
+# HBM bytes per launch of the dominant kernel are not measurable from inside this script: they come from two
+# rocprofv3 --pmc runs of it (FETCH_SIZE, WRITE_SIZE), scaled by what the same counters read for a copy of known
+# size, and are kept with their command, date and source commit in profiles/traffic.json.  A workload / schedule /
+# kernel without an entry there reports traffic = null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def measured_traffic(workload, schedule, kernel):
+    try:
+        with open(TRAFFIC_FILE) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None
+    for e in table.get("entries", []):
+        if e.get("workload") == workload and e.get("schedule") == schedule and e.get("kernel") == kernel:
+            return e
+    return None
 
 
 def parse():
@@ -130,6 +142,8 @@ def cpu_baseline(w, target_flop=6e12):
     for l in order:
         spec = w.layers[l]
         X, dY = W.make_layer(w, l)
+        if X.dtype == np.float16:     # the oracle takes stored values widened exactly
+            X, dY = X.astype(np.float32), dY.astype(np.float32)
         t0 = time.perf_counter()
         O.linear_dp_grad(X, dY, w.C, w.sigma, w.layer_seed(l), l)
         dt += time.perf_counter() - t0
@@ -157,7 +171,8 @@ def main():
     F.lib()   # fail loudly if the HIP library is missing
     w = W.WORKLOADS[args.workload]
     dev = "cuda:0"
-    dtype_code = F.BF16 if w.dtype == "bf16" else F.F32
+    dtype_code = {"bf16": F.BF16, "f16": F.F16, "fp32": F.F32}[w.dtype]
+    peak = PEAK_MFMA_TFLOPS[w.dtype]
     layers, keep = [], []
     shared = {}
     for l, spec in enumerate(w.layers):
@@ -183,6 +198,7 @@ def main():
 
     ms = time_steps(step, args.steps, args.warmup)
     used = F.flashdp_last_schedule()
+    kernel = F.flashdp_last_kernel()
     flops = float(w.flops())
     tflops = flops / ms / 1e9
     ms_median, ms_min = time_each(step, args.steps, 2)   # spread of single steps, outside the timed region above
@@ -200,10 +216,12 @@ def main():
         hw_flops = flops + sum(float(w.B) * w.T * (w.T + 128) * (s.d_in + s.d_out) for s in w.layers)
     traffic_key = "scratch" if used == "overlap" else used
     n_launch = len(w.layers)
+    what = {"scratch": "per-sample contraction + norm + spill", "twopass": "per-sample contraction + norm (first of two passes)",
+            "explicit": "per-sample contraction, fp32 gradients materialised", "ghost": "Gram-matrix norms"}[traffic_key]
     roofline = {
-        "bound": "mfma", "kernel": "gemm_mfma_dma_kernel (per-sample contraction + norm + spill)",
-        "achieved": round(flops / ms_contract / 1e9, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(flops / ms_contract / 1e9 / PEAK_BF16_TFLOPS, 4),
+        "bound": "mfma", "kernel": f"{'gram_norm_mfma_kernel' if used == 'ghost' else kernel} ({what})",
+        "achieved": round(flops / ms_contract / 1e9, 2), "peak": peak, "unit": "TFLOP/s",
+        "frac": round(flops / ms_contract / 1e9 / peak, 4),
         "launches_per_step": n_launch, "avg_launch_ms": round(ms_contract / n_launch, 4),
         "flops_per_launch": flops / n_launch, "traffic": None,
     }
@@ -211,11 +229,15 @@ def main():
         probe = mfma_only(F, torch, dev)
         roofline["mfma_only"] = probe
         roofline["frac_of_mfma_only_random"] = round(flops / ms_contract / 1e9 / probe["random_tflops"], 4)
-    mt = MEASURED_TRAFFIC.get((w.name, traffic_key))
+    mt = measured_traffic(w.name, traffic_key, kernel)
     if mt:
         roofline["traffic"] = mt["read_bytes"] + mt["write_bytes"]
-        roofline["traffic_detail"] = dict(mt, algorithmic_read_bytes=sum(2.0 * w.B * w.T * (s.d_in + s.d_out) for s in w.layers) / n_launch,
-                                          algorithmic_write_bytes=sum(2.0 * w.B * s.d_in * s.d_out for s in w.layers) / n_launch)
+        esz = 4.0 if w.dtype == "fp32" else 2.0
+        roofline["traffic_detail"] = {
+            "read_bytes": mt["read_bytes"], "write_bytes": mt["write_bytes"], "source": "profiles/traffic.json",
+            "measured_at_commit": mt.get("commit"), "measured_on": mt.get("date"),
+            "algorithmic_read_bytes": sum(esz * w.B * w.T * (s.d_in + s.d_out) for s in w.layers) / n_launch,
+            "algorithmic_write_bytes": sum(esz * w.B * s.d_in * s.d_out for s in w.layers) / n_launch}
 
     result = {
         "metric": "dp_weight_grad_tflops", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
@@ -225,9 +247,10 @@ def main():
                    "layers": [f"{s.name}:{s.d_in}->{s.d_out}" for s in w.layers],
                    "C": w.C, "sigma": w.sigma, "schedule": used, "shared_x": bool(args.share_x)},
         "ms_per_step_median": round(ms_median, 4), "ms_per_step_min": round(ms_min, 4),
-        "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "frac_of_mfma_peak": round(tflops / peak, 4),
         "hardware_flops_per_step": hw_flops,
-        "stage_ms": {"contract": round(ms_contract, 4), "aggregate_and_noise": round(ms_aggregate, 4)},
+        "stage_ms": {"contract": round(ms_contract, 4), "aggregate_and_noise": round(ms_aggregate, 4),
+                     "exposed_beyond_contract": round(ms - ms_contract, 4)},
         "roofline": roofline,
     }
 

@@ -40,9 +40,17 @@
  *     take a slower generic kernel.
  *   - NaN/Inf in the inputs propagate to out_norms / out_grad: a sample with a NaN norm gets a NaN clip
  *     factor and so turns the whole of out_grad into NaN (it is never let through unclipped).
- *   - Return value: FLASHDP_OK (0) or a negative flashdp_status; on error nothing is enqueued.
+ *     A per-sample gradient that overflows fp32 (infinite norm) poisons out_grad with NaN/Inf under every
+ *     schedule.  TWOPASS and GHOST rescale the running sum by c_i / c_(i+1) at sample boundaries; two
+ *     consecutive clip factors further apart than about 1e38 (a norm beyond 1e38 * C) overflow that ratio and
+ *     give Inf/NaN as well, where SCRATCH / OVERLAP / EXPLICIT still give the finite result.
+ *   - Return value: FLASHDP_OK (0) or a negative flashdp_status.  Argument errors (everything but
+ *     FLASHDP_HIP_ERROR) are found before anything is enqueued; a FLASHDP_HIP_ERROR comes from the runtime
+ *     while enqueuing, and kernels of earlier layers or stages of the same call may then already be enqueued:
+ *     treat the outputs of that call as undefined.
  *
- * Environment overrides, read at every call (measurement aids, not needed in normal use):
+ * Environment overrides (measurement aids, not needed in normal use), read once per process at the first call;
+ * with FLASHDP_DEBUG_ENV=1 set at that moment they are read again at every call:
  *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit | ghost   replaces the schedule argument;
  *   FLASHDP_TILE = 2 | 3 | 4 | 6 forces the matrix-core kernel (256x256 with 64-deep k-tiles, 128x128,
  *                                256x256 with 32-deep k-tiles - these three stage tiles through registers -,
@@ -210,6 +218,11 @@ int flashdp_release(void);
 
 /* Name of the schedule the last call on this thread used: "twopass", "scratch", "overlap", "explicit" or "ghost" ("none" before any). */
 const char* flashdp_last_schedule(void);
+
+/* Name of the contraction kernel the last layer enqueued on this thread took (the per-sample pass of Algorithm 1):
+ * "gemm_mfma_dma_kernel" (16-bit inputs, tiles loaded straight into LDS), "gemm_mfma_kernel" (16-bit, register-staged,
+ * small shapes), "gemm_mfma_f32_kernel" (fp32 inputs), "gemm_simple_kernel" (any shape); "none" before any call. */
+const char* flashdp_last_kernel(void);
 
 const char* flashdp_status_string(int status);
 int flashdp_version(void);   /* major*10000 + minor*100 + patch */

@@ -82,6 +82,7 @@ def lib() -> ctypes.CDLL:
                   "flashdp_set_schedule", "flashdp_set_stages", "flashdp_release", "flashdp_version"):
             getattr(L, n).restype = ci
         L.flashdp_last_schedule.restype = ctypes.c_char_p
+        L.flashdp_last_kernel.restype = ctypes.c_char_p
         L.flashdp_status_string.argtypes = [ci]
         L.flashdp_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -158,6 +159,10 @@ def flashdp_release():
 
 def flashdp_last_schedule() -> str:
     return lib().flashdp_last_schedule().decode()
+
+
+def flashdp_last_kernel() -> str:
+    return lib().flashdp_last_kernel().decode()
 
 
 def flashdp_version() -> int:

@@ -42,6 +42,7 @@ struct Context {
   int schedule = FLASHDP_SCHEDULE_AUTO;
   int stages = FLASHDP_STAGE_ALL;
   const char* last_schedule = "none";
+  const char* last_kernel = "none";
 };
 thread_local Context g_ctx;
 
@@ -97,9 +98,41 @@ struct Plan {
   int accum_tiles_m, accum_tiles_n;   // the accumulating pass has one workgroup per tile (not per sample and tile)
 };
 
-int env_int(const char* name, int dflt) {
-  const char* s = std::getenv(name);
-  return (s && *s) ? std::atoi(s) : dflt;
+// Environment overrides (measurement aids).  Read once per process, at the first call that needs them; with
+// FLASHDP_DEBUG_ENV=1 in the environment at that moment they are read again at every call instead (the test
+// suite switches kernels and schedules between calls this way).
+struct EnvOverrides { int tile = 0; int overlap_grid = 512; int schedule = -1; };
+
+int parse_schedule_name(const char* s) {
+  if (!s || !*s) return -1;
+  if (!std::strcmp(s, "twopass")) return FLASHDP_SCHEDULE_TWOPASS;
+  if (!std::strcmp(s, "scratch")) return FLASHDP_SCHEDULE_SCRATCH;
+  if (!std::strcmp(s, "explicit")) return FLASHDP_SCHEDULE_EXPLICIT;
+  if (!std::strcmp(s, "overlap")) return FLASHDP_SCHEDULE_OVERLAP;
+  if (!std::strcmp(s, "ghost")) return FLASHDP_SCHEDULE_GHOST;
+  return -1;
+}
+
+EnvOverrides read_env() {
+  EnvOverrides e;
+  const char* s = std::getenv("FLASHDP_TILE");
+  if (s && *s) e.tile = std::atoi(s);
+  s = std::getenv("FLASHDP_OVERLAP_GRID");
+  if (s && *s) e.overlap_grid = std::atoi(s);
+  e.schedule = parse_schedule_name(std::getenv("FLASHDP_SCHEDULE"));
+  return e;
+}
+
+EnvOverrides env() {
+  static std::once_flag once;
+  static EnvOverrides cached;
+  static bool live = false;
+  std::call_once(once, [] {
+    const char* d = std::getenv("FLASHDP_DEBUG_ENV");
+    live = d && d[0] == '1';
+    cached = read_env();
+  });
+  return live ? read_env() : cached;
 }
 
 Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
@@ -108,13 +141,13 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
                        (T + 320) * (P > D ? P : D) * 2 < (int64_t(1) << 31);   // incl. the parked prefetches past the end
   // fp32 inputs: fp32 matrix-core kernel when rows are 16-byte multiples and the problem spans a few tiles
   const bool f32_ok = dtype == FLASHDP_F32 && P % 4 == 0 && D % 4 == 0 && P * D >= 128 * 128 &&
-                      (T + 48) * (P > D ? P : D) * 4 < (int64_t(1) << 31) && env_int("FLASHDP_TILE", 0) != -1;
+                      (T + 48) * (P > D ? P : D) * 4 < (int64_t(1) << 31) && env().tile != -1;
   if (f32_ok) {
     p.path = p.accum_path = PATH_F32; p.bm = p.bn = 256;
   } else if (!mfma_ok) {
     p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
-    int choice = env_int("FLASHDP_TILE", 0);
+    int choice = env().tile;
     if (choice != PATH_DMA && (choice < PATH_256x8 || choice > PATH_256x8k32)) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
     if (choice == 0) {
       // The 256x256 direct-to-LDS kernel unless the problem has too few such work items to occupy the chip:
@@ -131,7 +164,7 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     p.path = (Path)choice;
     p.accum_path = p.path;
     // ... so it needs about the same number of 256x256 tiles by itself before the large tile pays
-    if (env_int("FLASHDP_TILE", 0) == 0 && p.path == PATH_DMA && ((D + 255) / 256) * ((P + 255) / 256) < 128) p.accum_path = PATH_128x4;
+    if (env().tile == 0 && p.path == PATH_DMA && ((D + 255) / 256) * ((P + 255) / 256) < 128) p.accum_path = PATH_128x4;
     p.bm = p.bn = (p.path == PATH_128x4) ? 128 : 256;
   }
   p.tiles_m = (int)((D + p.bm - 1) / p.bm);
@@ -140,6 +173,15 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
   p.accum_tiles_m = (int)((D + abm - 1) / abm);
   p.accum_tiles_n = (int)((P + abn - 1) / abn);
   return p;
+}
+
+const char* path_kernel_name(Path p) {
+  switch (p) {
+    case PATH_DMA: return "gemm_mfma_dma_kernel";
+    case PATH_F32: return "gemm_mfma_f32_kernel";
+    case PATH_SIMPLE: return "gemm_simple_kernel";
+    default: return "gemm_mfma_kernel";
+  }
 }
 
 struct WsLayout { size_t factors, partials, scratch, total; };
@@ -178,22 +220,28 @@ WsLayout ws_layout(const Plan& p, int64_t B, int64_t T, int64_t P, int64_t D, in
   return w;
 }
 
-// Launches one of the tiled matrix-core kernels: raises its dynamic-LDS limit once, grid = tiles (x samples for the
-// per-sample modes).
+// Raises a kernel's dynamic-LDS limit, once per device and kernel (under a lock: any thread, any device).
+hipError_t ensure_lds_limit(const void* kern, int bytes) {
+  static std::mutex m;
+  static std::map<std::pair<int, const void*>, bool> attr_set;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(m);
+  bool& done = attr_set[std::make_pair(dev, kern)];
+  if (!done) {
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    done = true;
+  }
+  return hipSuccess;
+}
+
+// Launches one of the tiled matrix-core kernels: grid = tiles (x samples for the per-sample modes).
 template <typename Cfg>
 hipError_t launch_tiled(void (*kern)(GemmArgs), int mode, const GemmArgs& a, hipStream_t st, bool lockstep = false) {
-  static std::mutex m;
-  static std::map<std::pair<int, const void*>, bool> attr_set;   // per device and kernel instantiation
   {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
-    std::lock_guard<std::mutex> lock(m);
-    bool& done = attr_set[std::make_pair(dev, reinterpret_cast<const void*>(kern))];
-    if (!done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-      if (e != hipSuccess) return e;
-      done = true;
-    }
+    hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(kern), Cfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
   }
   const int tiles = a.tiles_m * a.tiles_n;
   // lockstep: the per-sample grid in blocks of 32 tiles dealt to the XCDs in turn (see shared_block_item)
@@ -264,14 +312,9 @@ hipError_t launch_aggregate(int dtype, const void* scratch, const float* factors
 hipError_t launch_gram(int dtype, bool mfma, const GramArgs& g, hipStream_t st) {
   const unsigned grid = (unsigned)((int64_t)g.B * g.n_tri);
   if (mfma) {
-    static bool attr_set[2] = {false, false};
-    const int which = dtype == FLASHDP_BF16 ? 0 : 1;
-    auto kern = which == 0 ? gram_norm_mfma_kernel<DT_BF16> : gram_norm_mfma_kernel<DT_F16>;
-    if (!attr_set[which]) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, GramCfg::LDS_BYTES);
-      if (e != hipSuccess) return e;
-      attr_set[which] = true;
-    }
+    auto kern = dtype == FLASHDP_BF16 ? gram_norm_mfma_kernel<DT_BF16> : gram_norm_mfma_kernel<DT_F16>;
+    hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(kern), GramCfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(GramCfg::NT), GramCfg::LDS_BYTES, st, g);
   } else if (dtype == FLASHDP_BF16) {
     hipLaunchKernelGGL((gram_norm_simple_kernel<DT_BF16>), dim3(grid), dim3(256), 0, st, g);
@@ -334,15 +377,8 @@ int owned_workspace(size_t need, void** ptr, size_t* bytes) {
 }
 
 int resolve_schedule(int schedule) {
-  const char* s = std::getenv("FLASHDP_SCHEDULE");
-  if (s && *s) {
-    if (!std::strcmp(s, "twopass")) return FLASHDP_SCHEDULE_TWOPASS;
-    if (!std::strcmp(s, "scratch")) return FLASHDP_SCHEDULE_SCRATCH;
-    if (!std::strcmp(s, "explicit")) return FLASHDP_SCHEDULE_EXPLICIT;
-    if (!std::strcmp(s, "overlap")) return FLASHDP_SCHEDULE_OVERLAP;
-    if (!std::strcmp(s, "ghost")) return FLASHDP_SCHEDULE_GHOST;
-  }
-  return schedule;
+  const int forced = env().schedule;
+  return forced >= 0 ? forced : schedule;
 }
 
 size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mode) {
@@ -375,6 +411,7 @@ int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mod
   const int tiles = plan.tiles_m * plan.tiles_n;
   const size_t S = (size_t)D * P;
   const float noise_scale = add_noise ? L.sigma * L.C : 0.0f;
+  g_ctx.last_kernel = path_kernel_name(plan.path);
 
   if (mode == FLASHDP_SCHEDULE_EXPLICIT) {
     // The explicit four-stage flow of Appendix B.2, every stage a kernel of its own with the fp32
@@ -509,7 +546,7 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
       side->ready.push_back(e1);
       side->done.push_back(e2);
     }
-    const int grid = env_int("FLASHDP_OVERLAP_GRID", 512);
+    const int grid = env().overlap_grid;
     // Layers are independent, so they are taken largest first: the one aggregation that has nothing to hide
     // behind (the last) is then the smallest.
     std::vector<int> order(n_layers);
@@ -707,6 +744,8 @@ int flashdp_release(void) {
 }
 
 const char* flashdp_last_schedule(void) { return g_ctx.last_schedule; }
+
+const char* flashdp_last_kernel(void) { return g_ctx.last_kernel; }
 
 const char* flashdp_status_string(int status) {
   switch (status) {

@@ -200,23 +200,17 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16_t (&acc)
   if constexpr (MODE == MODE_NORM || MODE == MODE_SPILL) {
     // intra-block reduction of the squared norm: lane chain -> wave shuffle -> LDS across waves.
     // Rows/columns beyond D/P were loaded as zeros and add nothing.
-    float ss = 0.0f;
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) ss = fmaf(acc[i][j][e], acc[i][j][e], ss);
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
     // The operand tiles are dead after the barrier that follows the main loop; LDS now stages the
     // 16-bit tile (row pitch BN + 8 elements) so that it leaves the chip in full rows, and holds the
     // per-wave partial sums behind it.
     constexpr int EP = BN + 8;                               // pitch in elements: 16-byte aligned rows
     static_assert(BM * EP * 2 + 64 <= Cfg::LDS_BYTES, "epilogue staging must fit in the operand buffers");
     float* red = (float*)(lds + BM * EP);
-    if (lane == 0) red[wave] = ss;
+    float ss = 0.0f;
     if constexpr (MODE == MODE_SPILL) {
+      // The norm is taken of the tile AS PARKED (after the rounding to bfloat16), not of the fp32 accumulators:
+      // the clip factor then bounds the norm of exactly what the aggregation sums, so that every clipped
+      // per-sample contribution is <= C (the sensitivity bound of Algorithm 1) and not C (1 + 2^-9).
       unsigned short* st = lds + (wave_m * Cfg::TM + (lane & 31)) * EP + wave_n * Cfg::TN + 4 * (lane >> 5);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
@@ -229,9 +223,22 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16_t (&acc)
             // bound, and fp16's range (65504) would turn a large one into inf
             v.x = pack2_16bit<DT_BF16>(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
             v.y = pack2_16bit<DT_BF16>(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            const float r0 = __builtin_bit_cast(float, v.x << 16), r1 = __builtin_bit_cast(float, v.x & 0xFFFF0000u);
+            const float r2 = __builtin_bit_cast(float, v.y << 16), r3 = __builtin_bit_cast(float, v.y & 0xFFFF0000u);
+            ss = fmaf(r0, r0, ss); ss = fmaf(r1, r1, ss); ss = fmaf(r2, r2, ss); ss = fmaf(r3, r3, ss);
             *(uint2*)(st + (i * 32) * EP + j * 32 + 8 * q) = v;
           }
+    } else {
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) ss = fmaf(acc[i][j][e], acc[i][j][e], ss);
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if (lane == 0) red[wave] = ss;
     __syncthreads();
     if (tid == 0) {
       float tot = 0.0f;

@@ -20,6 +20,17 @@ __device__ __forceinline__ float load_elem(const void* p, size_t idx) {
   }
 }
 
+// The value of v as the scratch keeps it (rounded to bfloat16 for 16-bit inputs, unchanged for fp32): the
+// squared norm of the scratch schedule is taken of these, so that the clip factor bounds what is summed.
+template <int DT>
+__device__ __forceinline__ float as_parked(float v) {
+  if constexpr (DT == DT_F32) {
+    return v;
+  } else {
+    return __builtin_bit_cast(float, (uint32_t)to_16bit<DT_BF16>(v) << 16);
+  }
+}
+
 template <int DT>
 __device__ __forceinline__ void store_scratch(void* p, size_t idx, float v) {
   if constexpr (DT == DT_F32) {
@@ -94,7 +105,10 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) ss = fmaf(acc[i][j], acc[i][j], ss);
+      for (int j = 0; j < 4; ++j) {
+        const float g = (MODE == MODE_SPILL) ? as_parked<DT>(acc[i][j]) : acc[i][j];
+        ss = fmaf(g, g, ss);
+      }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
     if ((tid & 63) == 0) red[tid >> 6] = ss;

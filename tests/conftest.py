@@ -7,6 +7,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# the library re-reads FLASHDP_TILE / FLASHDP_SCHEDULE at every call only in this mode (the tests switch them between calls)
+os.environ.setdefault("FLASHDP_DEBUG_ENV", "1")
+
 GOLDEN = os.path.join(ROOT, "tests", "golden")
 
 

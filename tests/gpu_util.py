@@ -23,9 +23,41 @@ def rel_fro(got: np.ndarray, want: np.ndarray) -> float:
     return float(d / n) if n > 0 else float(d)
 
 
+def oracle_signal_and_bound(X, dY, C):
+    """The sigma = 0 result of the oracle composed from its own stage functions, sample by sample, together with
+    bound[e] = sum_i c_i |G_i[e]|: the magnitude the element-wise tolerance is scaled by (out[e] itself can be small
+    through cancellation between samples while each term, and hence each term's rounding error, is not).
+    Returns (out [D,P] fp64, norms [B] fp64, bound [D,P] fp64); out and norms are bit-identical to
+    O.linear_dp_grad(X, dY, C, 0, ...) (checked in the CPU suite)."""
+    from oracle import flashdp_oracle as O
+    out = bound = None
+    norms = np.zeros(X.shape[0])
+    for i in range(X.shape[0]):
+        G = O.per_sample_gradient(X[i], dY[i])
+        norms[i] = O.frobenius_norm(G)
+        G *= O.clip_factor(norms[i], float(C))
+        out = G.copy() if out is None else out + G
+        np.abs(G, out=G)
+        bound = G if bound is None else bound + G
+    return out, norms, bound
+
+
+def elementwise_excess(got: np.ndarray, want: np.ndarray, bound: np.ndarray, parked_16bit: bool):
+    """Element-wise check of the sigma = 0 signal.  Allowed |got - want| per element:
+      fp32 accumulation over T products and B samples:        1e-4 * rms(bound)   (every path)
+      plus, when the per-sample tile is parked as bfloat16:   2^-8 * bound[e]     (one rounding to 8 significant bits per term).
+    Returns (worst ratio err / allowed, flat index of the worst element); <= 1 passes."""
+    err = np.abs(got.astype(np.float64) - want)
+    allowed = 1e-4 * float(np.sqrt(np.mean(np.square(bound))))
+    allowed = allowed + (2.0 ** -8) * bound if parked_16bit else np.full_like(bound, allowed)
+    ratio = err / allowed
+    k = int(np.argmax(ratio))
+    return float(ratio.reshape(-1)[k]), k
+
+
 class env:
-    """Sets environment variables for the duration of a with-block (the library reads
-    FLASHDP_TILE / FLASHDP_SCHEDULE at every call)."""
+    """Sets environment variables for the duration of a with-block (with FLASHDP_DEBUG_ENV=1, which
+    conftest.py sets, the library reads FLASHDP_TILE / FLASHDP_SCHEDULE at every call)."""
 
     def __init__(self, **kv):
         self.kv = {k: v for k, v in kv.items() if v is not None}

@@ -266,3 +266,24 @@ def test_accumulation_over_micro_batches_equals_the_full_batch():
     a0, _ = O.accumulated_dp_grad([(X[:3], dY[:3]), (X[3:], dY[3:])], 1.0, 0.0, 5, 2)
     a1, _ = O.accumulated_dp_grad([(X[:3], dY[:3]), (X[3:], dY[3:])], 1.0, 0.7, 5, 2)
     assert np.allclose(a1 - a0, 0.7 * O.noise_field(5, 2, 12).reshape(3, 4), rtol=1e-12, atol=1e-14)
+
+
+def test_stage_by_stage_helper_of_the_gpu_tests_is_the_oracle():
+    """tests/gpu_util.oracle_signal_and_bound composes the oracle's own stage functions (so that it can also return
+    sum_i c_i |G_i|, the scale of the element-wise tolerance): its signal and norms must be the oracle's, bit for bit."""
+    from gpu_util import oracle_signal_and_bound, elementwise_excess
+    w = W.scaled_down(W.WORKLOADS["gpt2_small_mlp_up"], B=4, T=24, dims=[(40, 56)])
+    X, dY = W.make_layer(w, 0)
+    for C in (1.0, 1e9):
+        out, norms, bound = oracle_signal_and_bound(X, dY, C)
+        want, wn = O.linear_dp_grad(X, dY, C, 0.0, 1, 0)
+        assert np.array_equal(out, want) and np.array_equal(norms, wn)
+        assert np.all(bound >= np.abs(out) * (1 - 1e-12))
+    # the tolerance itself: an error of one bfloat16 rounding per term passes, a wrong element does not
+    out, norms, bound = oracle_signal_and_bound(X, dY, 1.0)
+    assert elementwise_excess(out + 0.9 * 2.0 ** -8 * bound, out, bound, True)[0] <= 1.0
+    bad = out.copy()
+    bad[3, 5] += 3e-2 * np.sqrt(np.mean(bound ** 2)) + 2.0 ** -7 * bound[3, 5]
+    worst, k = elementwise_excess(bad, out, bound, True)
+    assert worst > 1.0 and divmod(k, out.shape[1]) == (3, 5)
+    assert elementwise_excess(out + 2.0 ** -9 * bound, out, bound, False)[0] > 1.0

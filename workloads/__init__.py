@@ -15,6 +15,7 @@ threshold, the regime DP training lives in.
 Storage formats handed out:
   * "bf16": numpy uint16 arrays holding bfloat16 bit patterns (round-to-nearest-even
     from the float32 draw);
+  * "f16": numpy float16 arrays (round-to-nearest-even from the float32 draw);
   * "fp32": numpy float32 arrays.
 The consumer decides how to widen them; nothing here interprets them further.
 
@@ -45,7 +46,7 @@ class LayerSpec:
 @dataclass(frozen=True)
 class Workload:
     name: str
-    dtype: str            # "bf16" or "fp32"
+    dtype: str            # "bf16", "f16" or "fp32"
     B: int
     T: int
     layers: Tuple[LayerSpec, ...]
@@ -86,6 +87,13 @@ WORKLOADS: Dict[str, Workload] = {
     "llama7b_q_proj": Workload("llama7b_q_proj", "bf16", 4, 2048,
                                (LayerSpec("q_proj", 4096, 4096),),
                                1e-4, "loguniform", 1.0, 0.8, 3, 1),
+    # the precision variants of the mixed-precision experiment (Appendix D.2) on the configuration-3 layer
+    "llama7b_q_proj_fp32": Workload("llama7b_q_proj_fp32", "fp32", 4, 2048,
+                                    (LayerSpec("q_proj", 4096, 4096),),
+                                    1e-4, "loguniform", 1.0, 0.8, 3, 1),
+    "llama7b_q_proj_f16": Workload("llama7b_q_proj_f16", "f16", 4, 2048,
+                                   (LayerSpec("q_proj", 4096, 4096),),
+                                   1e-4, "loguniform", 1.0, 0.8, 3, 1),
     # configuration 4: Llama-13B MLP up_proj.
     "llama13b_up_proj": Workload("llama13b_up_proj", "bf16", 4, 2048,
                                  (LayerSpec("up_proj", 5120, 13824),),
@@ -119,6 +127,8 @@ def sample_scales(w: Workload, layer: int) -> np.ndarray:
 def _store(a32: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "bf16":
         return float32_to_bf16_bits(a32)
+    if dtype == "f16":
+        return a32.astype(np.float16)
     if dtype == "fp32":
         return a32
     raise ValueError(dtype)
@@ -143,7 +153,7 @@ def make_sample(w: Workload, layer: int, i: int, T: int | None = None):
 def make_layer(w: Workload, layer: int, threads: int = 8):
     """(X [B,T,P], dY [B,T,D]) for one layer, storage format per w.dtype."""
     spec = w.layers[layer]
-    np_dt = np.uint16 if w.dtype == "bf16" else np.float32
+    np_dt = {"bf16": np.uint16, "f16": np.float16, "fp32": np.float32}[w.dtype]
     X = np.empty((w.B, w.T, spec.d_in), dtype=np_dt)
     dY = np.empty((w.B, w.T, spec.d_out), dtype=np_dt)
 
@@ -177,7 +187,7 @@ def make_layer_device(w: Workload, layer: int, device: str = "cuda:0"):
     import torch
 
     spec = w.layers[layer]
-    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    dt = {"bf16": torch.bfloat16, "f16": torch.float16, "fp32": torch.float32}[w.dtype]
     g = torch.Generator(device=device)
     g.manual_seed((w.data_seed << 8) + layer)
     scales = torch.tensor(np.sqrt(w.dy_variance) * sample_scales(w, layer), dtype=torch.float32, device=device)
