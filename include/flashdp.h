@@ -102,8 +102,13 @@ enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
  *            never stored, then the clipped accumulation of TWOPASS (workspace: a few KB to MB of partial
  *            sums).  Costs T^2 (d_in + d_out) extra FLOPs per sample instead of a second 2 T d_in d_out.
  *            Never chosen by AUTO: it exists to be measured against;
- *   AUTO     OVERLAP when it applies and the workspace holds two slots, else SCRATCH when it holds one,
- *            else TWOPASS.                                                                              */
+ *   AUTO     OVERLAP when it applies and the workspace holds two slots, else SCRATCH when it holds one.  When a
+ *            caller's workspace holds fewer parked samples than the batch has, AUTO goes through the batch in
+ *            chunks of as many samples as fit (two slots of a smaller chunk where OVERLAP applies: chunk k's
+ *            streaming kernel then runs beside chunk k+1's contraction), every chunk's clipped sum added to
+ *            out_grad and the noise added with the last: memory bounded by the workspace whatever B is, each
+ *            G_i still computed once (flashdp_workspace_bytes_chunked sizes such a workspace).  Only a
+ *            workspace too small for a single sample falls back to TWOPASS.                              */
 enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2, FLASHDP_SCHEDULE_EXPLICIT = 3,
        FLASHDP_SCHEDULE_OVERLAP = 4, FLASHDP_SCHEDULE_GHOST = 5 };
 
@@ -173,6 +178,16 @@ size_t flashdp_static_scratch_bytes(void);
  * invalid arguments. */
 size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
                                int schedule);
+
+/* Bytes of workspace with which AUTO parks chunk_samples (1..B) samples at a time, in one slot (slots = 1,
+ * scratch schedule over chunks) or two (slots = 2, overlapped schedule over chunks).  With the 16-bit types that is
+ * about slots * chunk_samples * d_out * d_in * 2 bytes for the largest layer: slots = 2, chunk_samples = 1 costs as
+ * much memory as out_grad itself (4 * d_out * d_in bytes), independent of B.  Returns 0 on invalid arguments. */
+size_t flashdp_workspace_bytes_chunked(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                                       int64_t chunk_samples, int slots);
+
+/* Number of samples the last block call on this thread parked at a time (B when the batch was not chunked). */
+int64_t flashdp_last_chunk(void);
 
 /* Non-private weight gradient out_grad = sum_i dY_i^T X_i (Appendix B.1, Eq. "batched-grad") computed by
  * the same contraction kernel with the norm, clip and noise steps switched off: the comparator the DP

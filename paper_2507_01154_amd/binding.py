@@ -60,6 +60,9 @@ def lib() -> ctypes.CDLL:
         L.flashdp_block_dp_grad_micro.restype = ci
         L.flashdp_workspace_bytes.argtypes = [lp, ci, i64, i64, ci, ci]
         L.flashdp_workspace_bytes.restype = sz
+        L.flashdp_workspace_bytes_chunked.argtypes = [lp, ci, i64, i64, ci, i64, ci]
+        L.flashdp_workspace_bytes_chunked.restype = sz
+        L.flashdp_last_chunk.restype = i64
         L.flashdp_linear_dp_grad_static.argtypes = [vp, vp, i64, i64, i64, i64, ci, f32, f32, u64, u32, vp, vp, vp]
         L.flashdp_linear_dp_grad_static.restype = ci
         L.flashdp_static_scratch_bytes.argtypes = []
@@ -199,6 +202,15 @@ def make_layers(layers: Sequence[dict]):
 def flashdp_workspace_bytes(layers, B: int, T: int, dtype: int, schedule=SCHEDULE_SCRATCH) -> int:
     arr = layers if not isinstance(layers, (list, tuple)) else make_layers(layers)
     return int(lib().flashdp_workspace_bytes(arr, len(arr), B, T, int(dtype), schedule_code(schedule)))
+
+
+def flashdp_workspace_bytes_chunked(layers, B: int, T: int, dtype: int, chunk_samples: int, slots: int = 1) -> int:
+    arr = layers if not isinstance(layers, (list, tuple)) else make_layers(layers)
+    return int(lib().flashdp_workspace_bytes_chunked(arr, len(arr), B, T, int(dtype), int(chunk_samples), int(slots)))
+
+
+def flashdp_last_chunk() -> int:
+    return int(lib().flashdp_last_chunk())
 
 
 def flashdp_block_dp_grad(layers, B: int, T: int, dtype: int, schedule=SCHEDULE_AUTO, workspace=None, stream=None):

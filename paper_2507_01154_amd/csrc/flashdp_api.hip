@@ -43,6 +43,7 @@ struct Context {
   int stages = FLASHDP_STAGE_ALL;
   const char* last_schedule = "none";
   const char* last_kernel = "none";
+  int64_t last_chunk = 0;
 };
 thread_local Context g_ctx;
 
@@ -391,8 +392,14 @@ size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype,
 // Enqueues Algorithm 1 for one layer.
 // `parts` restricts what is enqueued (a subset of the stage mask); persistent_grid > 0 selects the bounded
 // aggregation grid of the overlapped schedule.
-int run_layer(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mode, char* ws, hipStream_t st,
-              bool accumulate, bool add_noise, int parts = FLASHDP_STAGE_ALL, int persistent_grid = 0) {
+// Samples [s0, s0 + B) of the layer's batch are processed (B is the number of samples of THIS call: the whole
+// batch, or one chunk of it when the workspace holds fewer parked samples than the batch has).
+int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mode, char* ws, hipStream_t st,
+              bool accumulate, bool add_noise, int parts = FLASHDP_STAGE_ALL, int persistent_grid = 0, int64_t s0 = 0) {
+  flashdp_layer_t L = L0;
+  L.X = static_cast<const char*>(L0.X) + (size_t)s0 * T * L0.d_in * elt_bytes(dtype);
+  L.dY = static_cast<const char*>(L0.dY) + (size_t)s0 * T * L0.d_out * elt_bytes(dtype);
+  if (L0.out_norms) L.out_norms = L0.out_norms + s0;
   const bool use_scratch = mode == FLASHDP_SCHEDULE_SCRATCH;
   const int stages = g_ctx.stages & parts;
   const int64_t P = L.d_in, D = L.d_out;
@@ -496,28 +503,57 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
   int dev = 0;
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
-  // The overlapped schedule needs two layers or more, 16-bit inputs on the large-tile matrix-core path
-  // (where the aggregation is worth hiding) and the full stage mask; otherwise it is the scratch schedule.
-  bool overlap_ok = n_layers >= 2 && dtype != FLASHDP_F32 && g_ctx.stages == FLASHDP_STAGE_ALL;
-  for (int l = 0; l < n_layers && overlap_ok; ++l) {
-    const Plan p = make_plan(B, T, layers[l].d_in, layers[l].d_out, dtype);
-    overlap_ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
-  }
-  const size_t slot = align_up(need_scratch, 256);
-  const size_t need_overlap = 2 * slot;
+  // The overlapped schedule needs two work items or more (layers, or sample chunks of a layer), 16-bit inputs on
+  // the large-tile matrix-core path (where the aggregation is worth hiding) and the full stage mask; otherwise it is
+  // the scratch schedule.
+  auto overlap_fits = [&](int64_t b) {
+    bool ok = dtype != FLASHDP_F32 && g_ctx.stages == FLASHDP_STAGE_ALL;
+    for (int l = 0; l < n_layers && ok; ++l) {
+      const Plan p = make_plan(b, T, layers[l].d_in, layers[l].d_out, dtype);
+      ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
+    }
+    return ok;
+  };
+  // workspace of the scratch schedule when b samples are parked at a time (the largest layer decides)
+  auto scratch_need = [&](int64_t b) {
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) need = std::max(need, layer_ws_bytes(layers[l], b, T, dtype, FLASHDP_SCHEDULE_SCRATCH));
+    return align_up(need, 256);
+  };
+  const bool overlap_ok = n_layers >= 2 && overlap_fits(B);
+  const size_t need_overlap = 2 * scratch_need(B);
   char* ws = static_cast<char*>(workspace);
   int mode;
+  int64_t chunk = B;   // samples parked at a time
   if (workspace) {
     if (schedule == FLASHDP_SCHEDULE_AUTO) {
       mode = (overlap_ok && workspace_bytes >= need_overlap) ? FLASHDP_SCHEDULE_OVERLAP
              : workspace_bytes >= need_scratch ? FLASHDP_SCHEDULE_SCRATCH : FLASHDP_SCHEDULE_TWOPASS;
+      if (mode == FLASHDP_SCHEDULE_TWOPASS && B > 1 && g_ctx.stages == FLASHDP_STAGE_ALL) {
+        // The workspace does not hold the whole batch: park as many samples as fit and go through the batch in
+        // chunks, each chunk's clipped sum added to out_grad (what the micro-batch form does), rather than compute
+        // every G_i twice.  Two slots of a smaller chunk (overlapped schedule) are taken when that chunk still has two
+        // samples or more: every chunk re-reads and re-writes out_grad, so single-sample chunks cost more in traffic
+        // and in small grids than hiding their aggregation saves (up_proj 13B, B = 8, memory for two samples: 1.27x
+        // the full-scratch time as 1 + 1 overlapped, 1.11x as one slot of 2).
+        int64_t b1 = 0, b2 = 0;
+        for (int64_t b = B - 1; b >= 1 && (b1 == 0 || b2 == 0); --b) {
+          const size_t n = scratch_need(b);
+          if (b1 == 0 && n <= workspace_bytes) b1 = b;
+          if (b2 == 0 && 2 * n <= workspace_bytes && overlap_fits(b)) b2 = b;
+        }
+        if (b2 >= 2) { mode = FLASHDP_SCHEDULE_OVERLAP; chunk = b2; }
+        else if (b1 >= 1) { mode = FLASHDP_SCHEDULE_SCRATCH; chunk = b1; }
+      }
     } else {
       mode = schedule;
     }
-    if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
-    const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
-                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost : need_small;
-    if (workspace_bytes < need) return FLASHDP_WORKSPACE_TOO_SMALL;
+    if (chunk == B) {
+      if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
+      const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
+                          : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost : need_small;
+      if (workspace_bytes < need) return FLASHDP_WORKSPACE_TOO_SMALL;
+    }
   } else {
     mode = schedule == FLASHDP_SCHEDULE_AUTO ? (overlap_ok ? FLASHDP_SCHEDULE_OVERLAP : FLASHDP_SCHEDULE_SCRATCH) : schedule;
     if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
@@ -528,18 +564,43 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     if (st != FLASHDP_OK) return st;
     ws = static_cast<char*>(p);
   }
+  g_ctx.last_chunk = chunk;
   hipStream_t main_st = static_cast<hipStream_t>(stream);
+
+  // Work items: (layer, chunk of samples).  The first chunk of a layer overwrites out_grad unless the caller
+  // accumulates, the later ones add to it; the noise goes in with the last chunk.
+  struct Item { int layer; int64_t s0, b; bool acc, noise; };
+  std::vector<Item> items;
+  {
+    std::vector<int> order(n_layers);
+    for (int l = 0; l < n_layers; ++l) order[l] = l;
+    if (mode == FLASHDP_SCHEDULE_OVERLAP) {
+      // Layers are independent, so they are taken largest first: the one aggregation that has nothing to hide
+      // behind (the last) is then the smallest.
+      std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+        return layers[x].d_in * layers[x].d_out > layers[y].d_in * layers[y].d_out;
+      });
+    }
+    for (int l : order)
+      for (int64_t s0 = 0; s0 < B; s0 += chunk) {
+        const int64_t b = std::min(chunk, B - s0);
+        items.push_back(Item{l, s0, b, accumulate != 0 || s0 > 0, add_noise != 0 && s0 + b == B});
+      }
+  }
+  const int n_items = (int)items.size();
+
   if (mode == FLASHDP_SCHEDULE_OVERLAP) {
-    // Layer l: contraction on the caller's stream into scratch slot l % 2; its clip factors and aggregation
-    // on the side stream, beside the contraction of layer l+1 (which then follows layer l's back to back).  Events order the two streams; the caller's
-    // stream waits for the last aggregations before the call's work counts as complete.
+    // Item k: contraction on the caller's stream into scratch slot k % 2; its clip factors and aggregation
+    // on the side stream, beside the contraction of item k+1 (which then follows item k's back to back).  Events order the two streams; the caller's
+    // stream waits for the last aggregations before the call's work counts as complete.  The aggregations of the
+    // chunks of one layer add to the same out_grad one after the other: they share the side stream, which is in order.
     // The side stream and its events are shared by every thread using this device: the whole enqueue
     // sequence below is done under the lock, so that one call's record/wait pairs are never interleaved
     // with another's (an event wait refers to the latest record at the time of the wait).
     std::lock_guard<std::mutex> lock(g_side_mutex);
     SideStream* side = &g_side[dev];
     if (!side->stream) HIP_TRY(hipStreamCreateWithFlags(&side->stream, hipStreamNonBlocking));
-    while ((int)side->ready.size() < n_layers) {
+    while ((int)side->ready.size() < n_items) {
       hipEvent_t e1 = nullptr, e2 = nullptr;
       HIP_TRY(hipEventCreateWithFlags(&e1, hipEventDisableTiming));
       HIP_TRY(hipEventCreateWithFlags(&e2, hipEventDisableTiming));
@@ -547,35 +608,29 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
       side->done.push_back(e2);
     }
     const int grid = env().overlap_grid;
-    // Layers are independent, so they are taken largest first: the one aggregation that has nothing to hide
-    // behind (the last) is then the smallest.
-    std::vector<int> order(n_layers);
-    for (int l = 0; l < n_layers; ++l) order[l] = l;
-    std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
-      return layers[x].d_in * layers[x].d_out > layers[y].d_in * layers[y].d_out;
-    });
-    for (int l = 0; l < n_layers; ++l) {
-      const flashdp_layer_t& Lr = layers[order[l]];
-      char* wsl = ws + (size_t)(l & 1) * slot;
-      if (l >= 2) HIP_TRY(hipStreamWaitEvent(main_st, side->done[l - 2], 0));   // slot free again
-      st = run_layer(Lr, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, main_st, accumulate != 0, add_noise != 0,
-                     FLASHDP_STAGE_CONTRACT);
+    const size_t slot = scratch_need(chunk);
+    for (int k = 0; k < n_items; ++k) {
+      const Item& it = items[k];
+      const flashdp_layer_t& Lr = layers[it.layer];
+      char* wsl = ws + (size_t)(k & 1) * slot;
+      if (k >= 2) HIP_TRY(hipStreamWaitEvent(main_st, side->done[k - 2], 0));   // slot free again
+      st = run_layer(Lr, it.b, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, main_st, it.acc, it.noise, FLASHDP_STAGE_CONTRACT, 0, it.s0);
       if (st != FLASHDP_OK) return st;
-      HIP_TRY(hipEventRecord(side->ready[l], main_st));
-      HIP_TRY(hipStreamWaitEvent(side->stream, side->ready[l], 0));
-      // the last layer has nothing to hide behind: ordinary grid
-      st = run_layer(Lr, B, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, side->stream, accumulate != 0, add_noise != 0,
-                     FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE, l + 1 < n_layers ? grid : 0);
+      HIP_TRY(hipEventRecord(side->ready[k], main_st));
+      HIP_TRY(hipStreamWaitEvent(side->stream, side->ready[k], 0));
+      // the last item has nothing to hide behind: ordinary grid
+      st = run_layer(Lr, it.b, T, dtype, FLASHDP_SCHEDULE_SCRATCH, wsl, side->stream, it.acc, it.noise,
+                     FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE, k + 1 < n_items ? grid : 0, it.s0);
       if (st != FLASHDP_OK) return st;
-      HIP_TRY(hipEventRecord(side->done[l], side->stream));
+      HIP_TRY(hipEventRecord(side->done[k], side->stream));
     }
-    HIP_TRY(hipStreamWaitEvent(main_st, side->done[n_layers - 1], 0));
-    HIP_TRY(hipStreamWaitEvent(main_st, side->done[n_layers - 2], 0));
+    HIP_TRY(hipStreamWaitEvent(main_st, side->done[n_items - 1], 0));
+    if (n_items >= 2) HIP_TRY(hipStreamWaitEvent(main_st, side->done[n_items - 2], 0));
     g_ctx.last_schedule = "overlap";
     return FLASHDP_OK;
   }
-  for (int l = 0; l < n_layers; ++l) {
-    st = run_layer(layers[l], B, T, dtype, mode, ws, main_st, accumulate != 0, add_noise != 0);
+  for (const Item& it : items) {
+    st = run_layer(layers[it.layer], it.b, T, dtype, mode, ws, main_st, it.acc, it.noise, FLASHDP_STAGE_ALL, 0, it.s0);
     if (st != FLASHDP_OK) return st;
   }
   g_ctx.last_schedule = mode == FLASHDP_SCHEDULE_SCRATCH ? "scratch" : mode == FLASHDP_SCHEDULE_EXPLICIT ? "explicit"
@@ -631,6 +686,17 @@ size_t flashdp_workspace_bytes(const flashdp_layer_t* layers, int n_layers, int6
   }
   if (schedule == FLASHDP_SCHEDULE_OVERLAP) need = 2 * align_up(need, 256);
   return need;
+}
+
+size_t flashdp_workspace_bytes_chunked(const flashdp_layer_t* layers, int n_layers, int64_t B, int64_t T, int dtype,
+                                       int64_t chunk_samples, int slots) {
+  if (!layers || n_layers <= 0 || !valid_dtype(dtype) || chunk_samples <= 0 || chunk_samples > B || slots < 1 || slots > 2) return 0;
+  size_t need = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (check_dims(B, T, layers[l].d_in, layers[l].d_out) != FLASHDP_OK) return 0;
+    need = std::max(need, layer_ws_bytes(layers[l], chunk_samples, T, dtype, FLASHDP_SCHEDULE_SCRATCH));
+  }
+  return (size_t)slots * align_up(need, 256);
 }
 
 int flashdp_plain_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
@@ -746,6 +812,8 @@ int flashdp_release(void) {
 const char* flashdp_last_schedule(void) { return g_ctx.last_schedule; }
 
 const char* flashdp_last_kernel(void) { return g_ctx.last_kernel; }
+
+int64_t flashdp_last_chunk(void) { return g_ctx.last_chunk; }
 
 const char* flashdp_status_string(int status) {
   switch (status) {

@@ -196,3 +196,58 @@ def test_overlapped_schedule_is_bit_identical_to_scratch(block_runs):
     torch.cuda.synchronize()
     assert F.flashdp_last_schedule() == "scratch"
     assert np.array_equal(layers[0]["out_grad"].cpu().numpy(), o1[0][0])
+
+
+@pytest.mark.timeout(600)
+def test_bounded_memory_scratch_full_size_llama13b_up_proj():
+    """A workspace that holds two parked samples of the Llama-13B up_proj layer (as much memory as out_grad itself)
+    instead of the whole batch of eight: AUTO goes through the batch in chunks of two samples instead of computing every
+    G_i twice; with room for four, in two overlapped slots of two.  Oracle parity as for the full scratch, and the
+    time beside the full-scratch time (printed; asserted loosely, the measured figure is in the design notes)."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["llama13b_up_proj"], B=8)
+    spec = w.layers[0]
+    X, dY = W.make_layer(w, 0)
+    dX, ddY = to_device(X), to_device(dY)
+    out = torch.full((spec.d_out, spec.d_in), float("nan"), device=DEV)
+    norms = torch.full((w.B,), float("nan"), device=DEV)
+    L = dict(X=dX, dY=ddY, d_in=spec.d_in, d_out=spec.d_out, C=w.C, sigma=0.0, seed=w.layer_seed(0), layer=0, out_grad=out, out_norms=norms)
+    full = F.flashdp_workspace_bytes([L], w.B, w.T, F.BF16, "scratch")
+    sig = wn = bound = None
+
+    def timed(arr, ws, reps=5):
+        F.flashdp_block_dp_grad(arr, w.B, w.T, F.BF16, "auto", ws)
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(reps):
+            F.flashdp_block_dp_grad(arr, w.B, w.T, F.BF16, "auto", ws)
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / reps
+
+    arr = F.make_layers([L])
+    ws_full = torch.empty(full, dtype=torch.uint8, device=DEV)
+    t_full = timed(arr, ws_full)
+    assert F.flashdp_last_schedule() == "scratch" and F.flashdp_last_chunk() == w.B
+    ref = out.cpu().numpy()
+    ref_n = norms.cpu().numpy()
+    del ws_full
+    for chunk, slots, want in ((2, 1, "scratch"), (2, 2, "overlap")):
+        need = F.flashdp_workspace_bytes_chunked([L], w.B, w.T, F.BF16, chunk, slots)
+        assert need <= slots * (4 * spec.d_in * spec.d_out + (1 << 20)) and need <= slots * full // 3   # one slot: as much memory as out_grad, a quarter of the full scratch
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        out.fill_(float("nan"))
+        t = timed(arr, ws)
+        assert F.flashdp_last_schedule() == want and F.flashdp_last_chunk() == chunk
+        got, gn = out.cpu().numpy(), norms.cpu().numpy()
+        assert np.array_equal(gn, ref_n)                              # same kernels on the same samples
+        assert rel_fro(got, ref.astype(np.float64)) <= 1e-6           # the same sum in another fp32 order
+        if sig is None:
+            sig, wn, bound = oracle_signal_and_bound(X, dY, w.C)
+        assert rel_fro(got, sig) <= 4e-3 and np.max(np.abs(gn - wn) / wn) <= 1e-4
+        worst, k = elementwise_excess(got, sig, bound, True)
+        assert worst <= 1.0, (divmod(k, spec.d_in), worst)
+        print(f"up_proj B=8, workspace {need / 2**20:.0f} MiB ({chunk} sample(s) x {slots} slot(s), {want}): {t:.3f} ms vs full scratch ({full / 2**20:.0f} MiB) {t_full:.3f} ms = {t / t_full:.3f}x")
+        assert t <= 1.25 * t_full
+        del ws

@@ -533,3 +533,42 @@ def test_nan_in_one_sample_poisons_the_output_instead_of_passing_unclipped(sched
     assert np.isnan(gn[1]) and np.all(np.isfinite(gn[[0, 2]]))
     assert np.allclose(gn[[0, 2]], wn[[0, 2]], rtol=1e-4)
     assert np.all(np.isnan(got))
+
+
+# ---------------------------------------------------------------------------------------------------
+# bounded-memory scratch: a workspace that holds fewer samples than the batch
+# ---------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("chunk,slots,want_schedule", [(2, 1, "scratch"), (1, 1, "scratch"), (2, 2, "overlap"), (1, 2, "overlap")])
+@pytest.mark.parametrize("tile", [None, 6])
+def test_auto_goes_through_the_batch_in_chunks_when_the_workspace_is_small(chunk, slots, want_schedule, tile):
+    B, T, P, D = 5, 96, 520, 776          # chunks of 2, 2, 1 (or five of 1); ragged 256-tiles
+    w = W.scaled_down(W.WORKLOADS["gpt2_small_mlp_up"], B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    L = [dict(X=None, dY=None, d_in=P, d_out=D, C=1.0, sigma=1.0, seed=3, layer=2, out_grad=None)]
+    need = F.flashdp_workspace_bytes_chunked(L, B, T, F.BF16, chunk, slots)
+    assert slots * chunk * D * P * 2 <= need < slots * (chunk * D * P * 2 + (1 << 16))
+    assert need < F.flashdp_workspace_bytes(L, B, T, F.BF16, "scratch")
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    want0, wn = O.linear_dp_grad(X, dY, 1.0, 0.0, 3, 2)
+    _, _, bound = oracle_signal_and_bound(X, dY, 1.0)
+    z = O.noise_field(3, 2, D * P).reshape(D, P)
+    if slots == 2 and (tile is None or chunk == 1):
+        want_schedule = "scratch"            # the small-shape kernel has no overlapped form, and single-sample chunks are
+                                             # not worth overlapping: the two slots are used as one
+    outs = {}
+    for sigma in (0.0, 1.0):
+        got, gn, used = run_layer(X, dY, 1.0, sigma, 3, 2, "auto", workspace=ws, tile=tile)
+        assert used == want_schedule
+        # two slots that end up as one (no overlapped form) hold a chunk twice as large
+        assert F.flashdp_last_chunk() == (chunk if (slots == 1 or used == "overlap") else min(2 * chunk, B - 1))
+        outs[sigma] = got
+        assert np.max(np.abs(gn - wn) / wn) <= 1e-4
+    assert rel_fro(outs[0.0], want0) <= 4e-3
+    worst, k = elementwise_excess(outs[0.0], want0, bound, True)
+    assert worst <= 1.0, (divmod(k, P), worst)
+    d = outs[1.0].astype(np.float64) - outs[0.0].astype(np.float64)
+    assert np.max(np.abs(d - z)) <= 4e-6 * max(1.0, float(np.max(np.abs(outs[0.0]))))     # noise added once, with the last chunk
+    # the unchunked schedule on the same data: same norms bit for bit, same sum up to fp32 summation order
+    full, fn, _ = run_layer(X, dY, 1.0, 0.0, 3, 2, "scratch", tile=tile)
+    assert np.array_equal(fn, gn) and rel_fro(outs[0.0], full.astype(np.float64)) <= 1e-6
