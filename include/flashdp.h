@@ -195,6 +195,20 @@ int64_t flashdp_last_chunk(void);
 int flashdp_plain_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                        int dtype, float* out_grad, void* stream);
 
+/* The same non-private gradient with the work balanced over the chip whatever the tile count: the output is cut into
+ * blocks of 32 tiles of 256 x 256, the eight XCDs are each dealt an equal, contiguous share of (block, k-tile) units,
+ * blocks at the edge of a share are cut along the reduction index (all samples' tokens, one sample after the other)
+ * and their fp32 pieces added by a second kernel in a fixed order (bit-repeatable, no atomics).  This is the
+ * comparator the DP path's ratio is quoted against: flashdp_plain_grad runs one workgroup per tile, and e.g. the 400
+ * tiles of a 5120 x 5120 layer leave its second round of 256 workgroups half empty.
+ * `workspace`: device memory of at least flashdp_plain_grad_balanced_workspace_bytes() (128 MiB, for the pieces of cut
+ * tiles), or NULL to use the library-owned workspace (allocated on first use, shared with the DP entry points: order
+ * such calls on one stream).  16-bit inputs with d_in and d_out multiples of 8; other problems are passed on to
+ * flashdp_plain_grad. */
+int flashdp_plain_grad_balanced(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                int dtype, float* out_grad, void* workspace, size_t workspace_bytes, void* stream);
+size_t flashdp_plain_grad_balanced_workspace_bytes(void);
+
 /* Fills z[0..n) (device, fp32) with the noise field of (seed, layer): the field that out_grad receives
  * scaled by sigma*C.  For checking the generator on its own. */
 int flashdp_noise_field(uint64_t seed, uint32_t layer, int64_t n, float* z, void* stream);

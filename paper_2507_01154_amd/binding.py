@@ -69,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.flashdp_static_scratch_bytes.restype = sz
         L.flashdp_plain_grad.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, vp]
         L.flashdp_plain_grad.restype = ci
+        L.flashdp_plain_grad_balanced.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, vp, sz, vp]
+        L.flashdp_plain_grad_balanced.restype = ci
+        L.flashdp_plain_grad_balanced_workspace_bytes.argtypes = []
+        L.flashdp_plain_grad_balanced_workspace_bytes.restype = sz
         L.flashdp_noise_field.argtypes = [u64, u32, i64, vp, vp]
         L.flashdp_noise_field.restype = ci
         L.flashdp_box_muller.argtypes = [vp, i64, vp, vp]
@@ -246,6 +250,16 @@ def flashdp_static_scratch_bytes() -> int:
 def flashdp_plain_grad(X, dY, B: int, T: int, d_in: int, d_out: int, dtype: int, out_grad, stream=None):
     _check(lib().flashdp_plain_grad(_ptr(X), _ptr(dY), B, T, d_in, d_out, int(dtype), _ptr(out_grad),
                                     _stream_handle(stream)), "flashdp_plain_grad")
+
+
+def flashdp_plain_grad_balanced(X, dY, B: int, T: int, d_in: int, d_out: int, dtype: int, out_grad, workspace=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().flashdp_plain_grad_balanced(_ptr(X), _ptr(dY), B, T, d_in, d_out, int(dtype), _ptr(out_grad),
+                                             _ptr(workspace), ws_bytes, _stream_handle(stream)), "flashdp_plain_grad_balanced")
+
+
+def flashdp_plain_grad_balanced_workspace_bytes() -> int:
+    return int(lib().flashdp_plain_grad_balanced_workspace_bytes())
 
 
 def flashdp_noise_field(seed: int, layer: int, n: int, z, stream=None):

@@ -17,6 +17,7 @@
 #include "gemm_mfma.hip.h"
 #include "gemm_mfma_dma.hip.h"
 #include "gemm_mfma_f32.hip.h"
+#include "gemm_mfma_streamk.hip.h"
 #include "gemm_simple.hip.h"
 #include "gram_norm.hip.h"
 #include "mfma_probe.hip.h"
@@ -714,6 +715,68 @@ int flashdp_plain_grad(const void* X, const void* dY, int64_t B, int64_t T, int6
   a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
   a.partials = nullptr; a.scratch = nullptr; a.factors = nullptr; a.out = out_grad; a.accumulate = 0;
   HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, static_cast<hipStream_t>(stream)));
+  return FLASHDP_OK;
+}
+
+size_t flashdp_plain_grad_balanced_workspace_bytes(void) {
+  return (size_t)STREAMK_SLOTS * STREAMK_WG_PER_XCD * 256 * 256 * sizeof(float);
+}
+
+int flashdp_plain_grad_balanced(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                int dtype, float* out_grad, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!X || !dY || !out_grad || !valid_dtype(dtype)) return FLASHDP_INVALID_ARGUMENT;
+  int st = check_dims(B, T, d_in, d_out);
+  if (st != FLASHDP_OK) return st;
+  if (!aligned16(X) || !aligned16(dY) || !aligned16(out_grad) || (workspace && !aligned16(workspace))) return FLASHDP_MISALIGNED;
+  // the balanced form exists for the large-tile 16-bit kernel; other problems take the ordinary plain gradient
+  const bool eligible = dtype != FLASHDP_F32 && d_in % 8 == 0 && d_out % 8 == 0 &&
+                        (T + 320) * (d_in > d_out ? d_in : d_out) * 2 < (int64_t(1) << 31);
+  if (!eligible) return flashdp_plain_grad(X, dY, B, T, d_in, d_out, dtype, out_grad, stream);
+  const size_t need = flashdp_plain_grad_balanced_workspace_bytes();
+  if (workspace && workspace_bytes < need) return FLASHDP_WORKSPACE_TOO_SMALL;
+  int dev = 0;
+  st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  if (!workspace) {
+    size_t got = 0;
+    st = owned_workspace(need, &workspace, &got);
+    if (st != FLASHDP_OK) return st;
+  }
+  StreamKArgs a;
+  a.X = X; a.dY = dY; a.B = (int)B; a.T = (int)T; a.P = (int)d_in; a.D = (int)d_out;
+  a.tiles_m = (int)((d_out + 255) / 256); a.tiles_n = (int)((d_in + 255) / 256);
+  const int tiles = a.tiles_m * a.tiles_n;
+  a.n_blocks = (tiles + STREAMK_WG_PER_XCD - 1) / STREAMK_WG_PER_XCD;
+  const int64_t nk = B * ((T + CfgDma::BK - 1) / CfgDma::BK);
+  const int64_t nk_pad = (nk + CfgDma::STAGES - 1) / CfgDma::STAGES * CfgDma::STAGES;
+  const int64_t total = (int64_t)a.n_blocks * nk_pad;
+  const int64_t per = ((total + STREAMK_XCDS - 1) / STREAMK_XCDS + CfgDma::STAGES - 1) / CfgDma::STAGES * CfgDma::STAGES;
+  if (nk_pad >= (int64_t(1) << 30) || per >= (int64_t(1) << 30)) return FLASHDP_UNSUPPORTED_SHAPE;
+  a.nk_pad = (int)nk_pad;
+  a.units_per_xcd = (int)per;
+  a.out = out_grad;
+  a.partial = static_cast<float*>(workspace);
+  // which pieces make up each cut block: the same walk as the kernel's, range by range (= in reduction order)
+  StreamKCuts cuts;
+  cuts.n = 0;
+  for (int x = 0; x < STREAMK_XCDS; ++x) {
+    streamk_walk(x, a.n_blocks, a.nk_pad, a.units_per_xcd, [&](const StreamKPiece& pc) {
+      if (pc.slot < 0) return;
+      int c = 0;
+      while (c < cuts.n && cuts.block[c] != pc.block) ++c;
+      if (c == cuts.n) { cuts.block[c] = pc.block; cuts.count[c] = 0; ++cuts.n; }
+      cuts.slot[c][cuts.count[c]++] = pc.slot;
+    });
+  }
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  auto kern = dtype == FLASHDP_BF16 ? gemm_mfma_streamk_kernel<CfgDma, DT_BF16> : gemm_mfma_streamk_kernel<CfgDma, DT_F16>;
+  HIP_TRY(ensure_lds_limit(reinterpret_cast<const void*>(kern), CfgDma::LDS_BYTES));
+  hipLaunchKernelGGL(kern, dim3(STREAMK_XCDS * STREAMK_WG_PER_XCD), dim3(CfgDma::NT), CfgDma::LDS_BYTES, hs, a);
+  HIP_TRY(hipGetLastError());
+  if (cuts.n > 0) {
+    hipLaunchKernelGGL(streamk_fixup_kernel, dim3((unsigned)(cuts.n * STREAMK_WG_PER_XCD)), dim3(256), 0, hs, a, cuts);
+    HIP_TRY(hipGetLastError());
+  }
   return FLASHDP_OK;
 }
 

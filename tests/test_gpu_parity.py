@@ -572,3 +572,40 @@ def test_auto_goes_through_the_batch_in_chunks_when_the_workspace_is_small(chunk
     # the unchunked schedule on the same data: same norms bit for bit, same sum up to fp32 summation order
     full, fn, _ = run_layer(X, dY, 1.0, 0.0, 3, 2, "scratch", tile=tile)
     assert np.array_equal(fn, gn) and rel_fro(outs[0.0], full.astype(np.float64)) <= 1e-6
+
+
+# ---------------------------------------------------------------------------------------------------
+# the balanced plain gradient (comparator of the DP ratio)
+# ---------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape", [
+    (3, 160, 264, 392),      # one ragged block of 4 tiles, 15 k-tiles: cut along the reduction index into 4 pieces
+    (2, 100, 1544, 2056),    # 63 tiles: a full block and a ragged one, each cut
+    (2, 64, 4096, 4096),     # 256 tiles = 8 blocks, one whole block per XCD: nothing is cut
+    (2, 192, 5120, 5120),    # 400 tiles = 12.5 blocks, 12 k-tiles each: whole blocks and cut blocks side by side
+    (1, 33, 264, 24),        # a single sample, T not a multiple of the k-tile, thin output
+])
+def test_balanced_plain_grad_is_the_batched_gradient(shape):
+    B, T, P, D = shape
+    w = W.scaled_down(W.WORKLOADS["gpt2_small_mlp_up"], B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    dX, ddY = to_device(X), to_device(dY)
+    want = O.widen(dY).reshape(B * T, D).T @ O.widen(X).reshape(B * T, P)        # Eq. batched-grad
+    ws = torch.empty(F.flashdp_plain_grad_balanced_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    outs = []
+    for rep in range(2):
+        out = torch.full((D, P), float("nan"), device=DEV)
+        F.flashdp_plain_grad_balanced(dX, ddY, B, T, P, D, F.BF16, out, ws)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    assert np.all(np.isfinite(outs[0])) and rel_fro(outs[0], want) <= 5e-6
+    err = np.abs(outs[0] - want)
+    assert np.max(err) <= 1e-4 * np.sqrt(np.mean(want ** 2)) + 1e-5 * np.max(np.abs(want))
+    assert np.array_equal(outs[0], outs[1])                                       # fixed-order sum of the pieces
+    ref = torch.full((D, P), float("nan"), device=DEV)
+    F.flashdp_plain_grad(dX, ddY, B, T, P, D, F.BF16, ref)
+    torch.cuda.synchronize()
+    assert rel_fro(outs[0], ref.cpu().numpy().astype(np.float64)) <= 2e-6
+    with pytest.raises(F.FlashDPError) as ei:
+        F.flashdp_plain_grad_balanced(dX, ddY, B, T, P, D, F.BF16, out, ws[: ws.numel() // 2])
+    assert ei.value.status == F.WORKSPACE_TOO_SMALL
