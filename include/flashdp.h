@@ -51,7 +51,7 @@
  *
  * Environment overrides (measurement aids, not needed in normal use), read once per process at the first call;
  * with FLASHDP_DEBUG_ENV=1 set at that moment they are read again at every call:
- *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit | ghost   replaces the schedule argument;
+ *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit | ghost | fused   replaces the schedule argument;
  *   FLASHDP_TILE = 2 | 3 | 4 | 6 forces the matrix-core kernel (256x256 with 64-deep k-tiles, 128x128,
  *                                256x256 with 32-deep k-tiles - these three stage tiles through registers -,
  *                                256x256 with 32-deep k-tiles loaded straight into LDS);
@@ -102,6 +102,15 @@ enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
  *            never stored, then the clipped accumulation of TWOPASS (workspace: a few KB to MB of partial
  *            sums).  Costs T^2 (d_in + d_out) extra FLOPs per sample instead of a second 2 T d_in d_out.
  *            Never chosen by AUTO: it exists to be measured against;
+ *   FUSED    Algorithm 1 in one launch with its block-wise synchronisation as a barrier across the grid (the
+ *            "ideal single-kernel solution" of Section 4.2): one workgroup owns one 256 x 256 output tile for all
+ *            samples, parks all but the last sample's tile (bfloat16), meets the other workgroups at a barrier in
+ *            memory once every squared-norm partial is written, and forms the clipped, noised sum of its tile from
+ *            its own parked tiles and the accumulators it still holds.  For layers whose tiles all fit on the chip
+ *            at once (d_out/256 * d_in/256 <= compute units, 16-bit inputs, B <= 16; e.g. 4096 x 4096); other
+ *            layers of the call take SCRATCH.  Workspace: (B - 1) * d_out * d_in * 2 bytes + partials.  The barrier
+ *            wait is bounded: if the workgroups are not co-resident (chip shared with long-running work) the call
+ *            still terminates, after about two seconds, with out_grad all NaN and an error flag in the workspace.
  *   AUTO     OVERLAP when it applies and the workspace holds two slots, else SCRATCH when it holds one.  When a
  *            caller's workspace holds fewer parked samples than the batch has, AUTO goes through the batch in
  *            chunks of as many samples as fit (two slots of a smaller chunk where OVERLAP applies: chunk k's
@@ -110,7 +119,7 @@ enum { FLASHDP_BF16 = 0, FLASHDP_F32 = 1, FLASHDP_F16 = 2 };
  *            G_i still computed once (flashdp_workspace_bytes_chunked sizes such a workspace).  Only a
  *            workspace too small for a single sample falls back to TWOPASS.                              */
 enum { FLASHDP_SCHEDULE_AUTO = 0, FLASHDP_SCHEDULE_TWOPASS = 1, FLASHDP_SCHEDULE_SCRATCH = 2, FLASHDP_SCHEDULE_EXPLICIT = 3,
-       FLASHDP_SCHEDULE_OVERLAP = 4, FLASHDP_SCHEDULE_GHOST = 5 };
+       FLASHDP_SCHEDULE_OVERLAP = 4, FLASHDP_SCHEDULE_GHOST = 5, FLASHDP_SCHEDULE_FUSED = 6 };
 
 /* One linear layer of a block (Appendix A.1, "Per-Layer Gradient Processing": every layer is clipped
  * by its own norm with its own C and sigma). */
@@ -245,7 +254,7 @@ int flashdp_set_stages(int mask);
 /* Frees the library-owned workspaces, side streams and events (synchronises the device first). */
 int flashdp_release(void);
 
-/* Name of the schedule the last call on this thread used: "twopass", "scratch", "overlap", "explicit" or "ghost" ("none" before any). */
+/* Name of the schedule the last call on this thread used: "twopass", "scratch", "overlap", "explicit", "ghost" or "fused" ("none" before any). */
 const char* flashdp_last_schedule(void);
 
 /* Name of the contraction kernel the last layer enqueued on this thread took (the per-sample pass of Algorithm 1):

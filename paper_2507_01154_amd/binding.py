@@ -14,8 +14,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libflashdp.so")
 
 BF16, F32, F16 = 0, 1, 2
-SCHEDULE_AUTO, SCHEDULE_TWOPASS, SCHEDULE_SCRATCH, SCHEDULE_EXPLICIT, SCHEDULE_OVERLAP, SCHEDULE_GHOST = 0, 1, 2, 3, 4, 5
-_SCHEDULES = {"auto": 0, "twopass": 1, "scratch": 2, "explicit": 3, "overlap": 4, "ghost": 5}
+SCHEDULE_AUTO, SCHEDULE_TWOPASS, SCHEDULE_SCRATCH, SCHEDULE_EXPLICIT, SCHEDULE_OVERLAP, SCHEDULE_GHOST, SCHEDULE_FUSED = 0, 1, 2, 3, 4, 5, 6
+_SCHEDULES = {"auto": 0, "twopass": 1, "scratch": 2, "explicit": 3, "overlap": 4, "ghost": 5, "fused": 6}
 
 OK = 0
 INVALID_ARGUMENT, MISALIGNED, UNSUPPORTED_SHAPE, WORKSPACE_TOO_SMALL, NO_DEVICE, HIP_ERROR = -1, -2, -3, -4, -5, -6

@@ -18,6 +18,7 @@
 #include "gemm_mfma_dma.hip.h"
 #include "gemm_mfma_f32.hip.h"
 #include "gemm_mfma_streamk.hip.h"
+#include "fused_dp.hip.h"
 #include "gemm_simple.hip.h"
 #include "gram_norm.hip.h"
 #include "mfma_probe.hip.h"
@@ -79,7 +80,7 @@ int static_scratch_ptr(int dev, char** ptr) {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == FLASHDP_BF16 || d == FLASHDP_F32 || d == FLASHDP_F16; }
-inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_GHOST; }
+inline bool valid_schedule(int s) { return s >= FLASHDP_SCHEDULE_AUTO && s <= FLASHDP_SCHEDULE_FUSED; }
 inline size_t elt_bytes(int dtype) { return dtype == FLASHDP_F32 ? 4 : 2; }
 
 // ---- kernel plans --------------------------------------------------------------------------------
@@ -112,6 +113,7 @@ int parse_schedule_name(const char* s) {
   if (!std::strcmp(s, "explicit")) return FLASHDP_SCHEDULE_EXPLICIT;
   if (!std::strcmp(s, "overlap")) return FLASHDP_SCHEDULE_OVERLAP;
   if (!std::strcmp(s, "ghost")) return FLASHDP_SCHEDULE_GHOST;
+  if (!std::strcmp(s, "fused")) return FLASHDP_SCHEDULE_FUSED;
   return -1;
 }
 
@@ -383,7 +385,48 @@ int resolve_schedule(int schedule) {
   return forced >= 0 ? forced : schedule;
 }
 
+// Number of compute units of the current device (looked up once per device).
+int device_cus() {
+  static std::mutex m;
+  static std::map<int, int> cus;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  std::lock_guard<std::mutex> lock(m);
+  auto it = cus.find(dev);
+  if (it == cus.end()) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    it = cus.emplace(dev, n).first;
+  }
+  return it->second;
+}
+
+// The single-launch form needs a workgroup per 256 x 256 tile resident at the same time (one per CU: its ring takes
+// most of a CU's LDS), 16-bit inputs on the matrix-core path, and clip factors for all samples in LDS.
+bool fused_ok(int64_t B, int64_t T, int64_t P, int64_t D, int dtype, int cus) {
+  const int64_t tiles = ((D + 255) / 256) * ((P + 255) / 256);
+  return dtype != FLASHDP_F32 && P % 8 == 0 && D % 8 == 0 && B <= 16 && tiles <= cus &&
+         (T + 320) * (P > D ? P : D) * 2 < (int64_t(1) << 31);
+}
+
+struct FusedWs { size_t sync, partials, scratch, total; };
+FusedWs fused_ws(int64_t B, int64_t P, int64_t D) {
+  const size_t tiles = (size_t)((D + 255) / 256) * ((P + 255) / 256);
+  FusedWs w;
+  w.sync = 0;
+  w.partials = 256;
+  w.scratch = w.partials + align_up((size_t)B * tiles * 8 * 4, 256);
+  w.total = w.scratch + align_up((size_t)(B > 1 ? B - 1 : 0) * D * P * 2, 256);
+  return w;
+}
+
 size_t layer_ws_bytes(const flashdp_layer_t& L, int64_t B, int64_t T, int dtype, int mode) {
+  if (mode == FLASHDP_SCHEDULE_FUSED) {
+    // a layer the single-launch form does not apply to takes the scratch schedule; without a device, assume 256 CUs
+    const int cus = device_cus();
+    if (fused_ok(B, T, L.d_in, L.d_out, dtype, cus > 0 ? cus : 256)) return fused_ws(B, L.d_in, L.d_out).total;
+    mode = FLASHDP_SCHEDULE_SCRATCH;
+  }
   const Plan p = make_plan(B, T, L.d_in, L.d_out, dtype);
   return ws_layout(p, B, T, L.d_in, L.d_out, dtype, mode).total;
 }
@@ -401,6 +444,30 @@ int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mo
   L.X = static_cast<const char*>(L0.X) + (size_t)s0 * T * L0.d_in * elt_bytes(dtype);
   L.dY = static_cast<const char*>(L0.dY) + (size_t)s0 * T * L0.d_out * elt_bytes(dtype);
   if (L0.out_norms) L.out_norms = L0.out_norms + s0;
+  if (mode == FLASHDP_SCHEDULE_FUSED) {
+    if (g_ctx.stages == FLASHDP_STAGE_ALL && parts == FLASHDP_STAGE_ALL && fused_ok(B, T, L.d_in, L.d_out, dtype, device_cus())) {
+      const FusedWs fw = fused_ws(B, L.d_in, L.d_out);
+      FusedArgs f;
+      f.X = L.X; f.dY = L.dY; f.B = (int)B; f.T = (int)T; f.P = (int)L.d_in; f.D = (int)L.d_out;
+      f.tiles_m = (int)((L.d_out + 255) / 256); f.tiles_n = (int)((L.d_in + 255) / 256);
+      f.C = L.C; f.noise_scale = add_noise ? L.sigma * L.C : 0.0f; f.seed = L.seed; f.layer = L.layer;
+      f.accumulate = accumulate ? 1 : 0;
+      f.sync = reinterpret_cast<unsigned int*>(ws + fw.sync);
+      f.partials = reinterpret_cast<float*>(ws + fw.partials);
+      f.scratch = ws + fw.scratch;
+      f.out = L.out_grad; f.out_norms = L.out_norms;
+      f.spin_limit = 1u << 21;   // about two seconds of 1 us naps
+      auto kern = dtype == FLASHDP_BF16 ? fused_dp_kernel<DT_BF16> : fused_dp_kernel<DT_F16>;
+      HIP_TRY(ensure_lds_limit(reinterpret_cast<const void*>(kern), FusedCfg::LDS_BYTES));
+      hipLaunchKernelGGL(fused_sync_reset_kernel, dim3(1), dim3(64), 0, st, f.sync);
+      HIP_TRY(hipGetLastError());
+      hipLaunchKernelGGL(kern, dim3((unsigned)(f.tiles_m * f.tiles_n)), dim3(FusedCfg::NT), FusedCfg::LDS_BYTES, st, f);
+      HIP_TRY(hipGetLastError());
+      g_ctx.last_kernel = "fused_dp_kernel";
+      return FLASHDP_OK;
+    }
+    mode = FLASHDP_SCHEDULE_SCRATCH;
+  }
   const bool use_scratch = mode == FLASHDP_SCHEDULE_SCRATCH;
   const int stages = g_ctx.stages & parts;
   const int64_t P = L.d_in, D = L.d_out;
@@ -490,8 +557,9 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
   }
   if (workspace && !aligned16(workspace)) return FLASHDP_MISALIGNED;
   schedule = resolve_schedule(schedule);
-  size_t need_scratch = 0, need_small = 0, need_explicit = 0, need_ghost = 0;
+  size_t need_scratch = 0, need_small = 0, need_explicit = 0, need_ghost = 0, need_fused = 0;
   for (int l = 0; l < n_layers; ++l) {
+    need_fused = std::max(need_fused, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_FUSED));
     need_scratch = std::max(need_scratch, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_SCRATCH));
     need_small = std::max(need_small, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_TWOPASS));
     need_explicit = std::max(need_explicit, layer_ws_bytes(layers[l], B, T, dtype, FLASHDP_SCHEDULE_EXPLICIT));
@@ -552,14 +620,16 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     if (chunk == B) {
       if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
       const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
-                          : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost : need_small;
+                          : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost
+                          : mode == FLASHDP_SCHEDULE_FUSED ? need_fused : need_small;
       if (workspace_bytes < need) return FLASHDP_WORKSPACE_TOO_SMALL;
     }
   } else {
     mode = schedule == FLASHDP_SCHEDULE_AUTO ? (overlap_ok ? FLASHDP_SCHEDULE_OVERLAP : FLASHDP_SCHEDULE_SCRATCH) : schedule;
     if (mode == FLASHDP_SCHEDULE_OVERLAP && !overlap_ok) mode = FLASHDP_SCHEDULE_SCRATCH;
     const size_t need = mode == FLASHDP_SCHEDULE_OVERLAP ? need_overlap : mode == FLASHDP_SCHEDULE_SCRATCH ? need_scratch
-                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost : need_small;
+                        : mode == FLASHDP_SCHEDULE_EXPLICIT ? need_explicit : mode == FLASHDP_SCHEDULE_GHOST ? need_ghost
+                        : mode == FLASHDP_SCHEDULE_FUSED ? need_fused : need_small;
     void* p = nullptr; size_t got = 0;
     st = owned_workspace(need, &p, &got);
     if (st != FLASHDP_OK) return st;
@@ -635,7 +705,7 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     if (st != FLASHDP_OK) return st;
   }
   g_ctx.last_schedule = mode == FLASHDP_SCHEDULE_SCRATCH ? "scratch" : mode == FLASHDP_SCHEDULE_EXPLICIT ? "explicit"
-                        : mode == FLASHDP_SCHEDULE_GHOST ? "ghost" : "twopass";
+                        : mode == FLASHDP_SCHEDULE_GHOST ? "ghost" : mode == FLASHDP_SCHEDULE_FUSED ? "fused" : "twopass";
   return FLASHDP_OK;
 }
 

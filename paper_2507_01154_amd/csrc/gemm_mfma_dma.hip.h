@@ -62,10 +62,11 @@ __device__ __forceinline__ void load_to_lds(const u32x4_t rsrc, uint32_t voff, u
 
 template <int N>
 __device__ __forceinline__ void wait_loads_outstanding() {
-  static_assert(N == 0 || N == 4 || N == 8, "count");
+  static_assert(N == 0 || N == 4 || N == 8 || N == 24, "count");
   if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
 }
 
 template <typename Cfg, int MODE, int DT>

@@ -24,7 +24,7 @@ def _layers(w, dims_idx):
     return layers
 
 
-@pytest.mark.parametrize("schedule,case", [("scratch", "gpt2"), ("twopass", "gpt2"), ("overlap", "block2")])
+@pytest.mark.parametrize("schedule,case", [("scratch", "gpt2"), ("twopass", "gpt2"), ("overlap", "block2"), ("fused", "gpt2")])
 def test_graph_capture_and_replay(schedule, case):
     if case == "gpt2":
         w = W.WORKLOADS["gpt2_small_mlp_up"]

@@ -34,7 +34,7 @@ TOL_NORM_STATED = 5e-3
 
 def tight_tol(dtype, schedule):
     if dtype == "fp32" or schedule in ("twopass", "explicit", "ghost"):
-        return 5e-5
+        return 5e-5        # (fp32 inputs asked for "fused" take the scratch schedule with an fp32 scratch)
     return 4e-3   # the 16-bit scratch is bfloat16 for bf16 and for fp16 inputs
 
 
@@ -54,7 +54,7 @@ def check_case(X, dY, C, sigma, seed, layer, dtype, schedule, tile=None, oracle=
     e_norm = float(np.max(np.abs(gn - wn) / np.maximum(wn, 1e-300))) if np.all(wn > 0) else float(np.max(np.abs(gn - wn)))
     assert e_sig <= TOL_STATED[dtype], (e_sig, used)
     assert e_sig <= tight_tol(dtype, used), (e_sig, used)
-    parked = dtype != "fp32" and used in ("scratch", "overlap")
+    parked = dtype != "fp32" and used in ("scratch", "overlap", "fused")
     worst, k = elementwise_excess(got0, want0, bound, parked)
     assert worst <= 1.0, (f"element {divmod(k, P)}: got {got0.reshape(-1)[k]!r}, want {want0.reshape(-1)[k]!r}, "
                           f"sum_i c_i|G_i| {bound.reshape(-1)[k]!r}, error / allowed = {worst:.3f}", used)
@@ -609,3 +609,74 @@ def test_balanced_plain_grad_is_the_batched_gradient(shape):
     with pytest.raises(F.FlashDPError) as ei:
         F.flashdp_plain_grad_balanced(dX, ddY, B, T, P, D, F.BF16, out, ws[: ws.numel() // 2])
     assert ei.value.status == F.WORKSPACE_TOO_SMALL
+
+
+# ---------------------------------------------------------------------------------------------------
+# the single-launch, grid-synchronised schedule
+# ---------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape", SMALL + [
+    (4, 100, 1160, 1320),    # 30 tiles, ragged in every dimension, T not a multiple of the k-tile: zero-padded k-tiles per sample
+    (1, 96, 520, 264),       # a single sample: nothing is parked, the accumulators go straight to the output
+    (9, 40, 264, 520),       # more samples than fingers on one hand
+])
+def test_fused_single_launch_schedule_bf16(shape):
+    B, T, P, D = shape
+    w = W.scaled_down(W.WORKLOADS["gpt2_small_mlp_up"], B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    e = check_case(X, dY, 1.0, 1.0, 11, 3, "bf16", "fused")
+    assert e[3] == "fused" and F.flashdp_last_kernel() == "fused_dp_kernel"
+    print(shape, "fused", e)
+
+
+def test_fused_schedule_branches_f16_accumulation_and_repeatability():
+    w = W.scaled_down(W.WORKLOADS["gpt2_small_mlp_up"], B=4, T=96, dims=[(264, 392)])
+    X, dY = W.make_layer(w, 0)
+    _, norms = O.linear_dp_grad(X, dY, 1.0, 0.0, 0)
+    C = float(np.sort(norms)[1] * 1.5)          # two samples below the threshold, two above
+    check_case(X, dY, C, 0.7, 5, 1, "bf16", "fused")
+    # fp16 inputs
+    rng = np.random.default_rng(17)
+    X16 = rng.standard_normal((3, 70, 136)).astype(np.float16)
+    dY16 = (rng.standard_normal((3, 70, 264)) * 0.05).astype(np.float16)
+    want = O.linear_dp_grad(X16.astype(np.float32), dY16.astype(np.float32), 1.0, 0.0, 9, 2)
+    check_case(X16, dY16, 1.0, 1.0, 9, 2, "f16", "fused", oracle=want)
+    # bit-repeatable (fixed-order reductions, barrier or not)
+    a = run_layer(X, dY, 1.0, 1.0, 7, 1, "fused")
+    b = run_layer(X, dY, 1.0, 1.0, 7, 1, "fused")
+    assert a[2] == "fused" and np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    # same norms as the scratch schedule up to the order of the partial sums (the last sample's comes from the fp32
+    # accumulators instead of the parked tile)
+    c = run_layer(X, dY, 1.0, 1.0, 7, 1, "scratch")
+    assert np.allclose(a[1][:-1], c[1][:-1], rtol=1e-6, atol=0) and abs(a[1][-1] - c[1][-1]) <= 1e-4 * c[1][-1]
+    # gradient accumulation over micro-batches through the fused schedule
+    B, T, P = X.shape
+    D = dY.shape[2]
+    out = torch.full((D, P), float("nan"), device=DEV)
+    mbs = [(X[:1], dY[:1]), (X[1:3], dY[1:3]), (X[3:], dY[3:])]
+    for k, (xm, ym) in enumerate(mbs):
+        nm = torch.empty((xm.shape[0],), device=DEV)
+        L = [dict(X=to_device(xm), dY=to_device(ym), d_in=P, d_out=D, C=1.0, sigma=0.9, seed=21, layer=4, out_grad=out, out_norms=nm)]
+        F.flashdp_block_dp_grad_micro(L, xm.shape[0], T, F.BF16, "fused", None, None, accumulate=k > 0, add_noise=k == len(mbs) - 1)
+        assert F.flashdp_last_schedule() == "fused"
+    torch.cuda.synchronize()
+    want, _ = O.accumulated_dp_grad(mbs, 1.0, 0.9, 21, 4)
+    sig, _ = O.accumulated_dp_grad(mbs, 1.0, 0.0, 21, 4)
+    z = O.noise_field(21, 4, D * P).reshape(D, P)
+    got = out.cpu().numpy()
+    assert rel_fro(got - 0.9 * z, sig) <= 4e-3 + 1e-4 and rel_fro(got, want) <= 1e-2
+
+
+def test_fused_schedule_falls_back_where_it_does_not_apply():
+    # fp32 inputs and layers with more 256 x 256 tiles than the chip has compute units take the scratch schedule
+    rng = np.random.default_rng(2)
+    X32 = rng.standard_normal((2, 33, 50)).astype(np.float32)
+    dY32 = (rng.standard_normal((2, 33, 70)) * 0.05).astype(np.float32)
+    got, gn, used = run_layer(X32, dY32, 1.0, 0.0, 1, 0, "fused")
+    assert used == "fused" and F.flashdp_last_kernel() != "fused_dp_kernel"
+    want, wn = O.linear_dp_grad(X32, dY32, 1.0, 0.0, 1, 0)
+    assert rel_fro(got, want) <= 5e-5
+    L = [dict(X=None, dY=None, d_in=5120, d_out=5120, C=1.0, sigma=1.0, seed=0, layer=0, out_grad=None)]
+    assert F.flashdp_workspace_bytes(L, 8, 2048, F.BF16, "fused") == F.flashdp_workspace_bytes(L, 8, 2048, F.BF16, "scratch")
+    L = [dict(X=None, dY=None, d_in=4096, d_out=4096, C=1.0, sigma=1.0, seed=0, layer=0, out_grad=None)]
+    assert F.flashdp_workspace_bytes(L, 4, 2048, F.BF16, "fused") < 0.8 * F.flashdp_workspace_bytes(L, 4, 2048, F.BF16, "scratch")   # one sample is never parked
