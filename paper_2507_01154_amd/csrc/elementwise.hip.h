@@ -10,29 +10,54 @@
 
 namespace flashdp {
 
-// One workgroup per sample: sums that sample's per-tile partial squared norms in a fixed order (fp64, so
-// the result does not depend on scheduling), then n_i = sqrt(.), c_i = 1 / max(1, n_i / C).
-// Replaces the per-block atomic add of the paper's inter-block reduce; the kernel boundary before it is
-// the block-wise synchronisation.
-__global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restrict__ partials, int tiles, float C,
-                                                           float* __restrict__ factors, float* __restrict__ out_norms) {
-  __shared__ double red[256];
-  const int i = blockIdx.x, tid = threadIdx.x;
+// Inter-block reduction of one sample's squared norm by one wave, in a fixed order so that the result does not
+// depend on scheduling or on which kernel does it: lane l adds partials l, l + 64, ... (fp64), then a butterfly
+// over the lanes (a + b == b + a, so every lane ends with the same bits).  Replaces the per-block atomic add of the
+// paper's inter-block reduce; the kernel boundary before it is the block-wise synchronisation.
+__device__ __forceinline__ double sample_norm_sq(const float* __restrict__ partials_i, int n, int lane) {
   double s = 0.0;
-  for (int k = tid; k < tiles; k += 256) s += (double)partials[(size_t)i * tiles + k];
-  red[tid] = s;
-  __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if (tid < w) red[tid] += red[tid + w];
-    __syncthreads();
-  }
-  if (tid == 0) {
-    const double n = sqrt(red[0]);
-    const double ratio = n / (double)C;
-    // written so that a NaN norm gives a NaN factor: a sample whose norm is unknown must not pass unclipped
-    factors[i] = (float)(1.0 / (ratio <= 1.0 ? 1.0 : ratio));
+  for (int k = lane; k < n; k += 64) s += (double)partials_i[k];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  return s;
+}
+
+// c_i = 1 / max(1, n_i / C), written so that a NaN norm gives a NaN factor: a sample whose norm is unknown must not
+// pass unclipped.
+__device__ __forceinline__ float clip_factor_of(double norm, float C) {
+  const double ratio = norm / (double)C;
+  return (float)(1.0 / (ratio <= 1.0 ? 1.0 : ratio));
+}
+
+// n_i = sqrt(sum of partials), c_i: one wave per sample, four samples per workgroup.  (The streaming kernels of the
+// scratch schedule do this themselves, see below; this kernel serves the schedules whose second pass is a contraction.)
+__global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restrict__ partials, int tiles, float C, int B,
+                                                           float* __restrict__ factors, float* __restrict__ out_norms) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= B) return;
+  const double n = sqrt(sample_norm_sq(partials + (size_t)i * tiles, tiles, lane));
+  if (lane == 0) {
+    factors[i] = clip_factor_of(n, C);
     if (out_norms) out_norms[i] = (float)n;
   }
+}
+
+// The same inside a streaming kernel: every workgroup (4 waves) works out all clip factors into LDS for itself, wave w
+// taking samples w, w + 4, ...; workgroup 0 also reports the norms.  Costs a workgroup about a microsecond and
+// B * tiles * 4 bytes of (cached) reads, and saves a kernel launch per layer; B <= MAX_FUSED_CLIP_B.
+constexpr int MAX_FUSED_CLIP_B = 64;
+__device__ __forceinline__ void clip_factors_to_lds(const float* __restrict__ partials, int tiles, float C, int B,
+                                                    float* lds_factors, float* __restrict__ out_norms) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = wave; i < B; i += 4) {
+    const double n = sqrt(sample_norm_sq(partials + (size_t)i * tiles, tiles, lane));
+    if (lane == 0) {
+      lds_factors[i] = clip_factor_of(n, C);
+      if (blockIdx.x == 0 && out_norms) out_norms[i] = (float)n;
+    }
+  }
+  __syncthreads();
 }
 
 template <int DT>
@@ -80,6 +105,20 @@ __global__ __launch_bounds__(256) void aggregate16_persistent_kernel(const void*
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += stride)
     aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
+}
+
+// The whole tail of Algorithm 1 after the block-wise synchronisation in one kernel: inter-block reduce and clip
+// factors (every workgroup for itself, into LDS), then the clipped batch sum with noise as above.
+template <int DT>
+__global__ __launch_bounds__(256) void clip_aggregate16_kernel(const void* __restrict__ scratch, const float* __restrict__ partials,
+                                                               int tiles, float C, float* __restrict__ out_norms, int B, size_t S,
+                                                               size_t n8, float noise_scale, uint64_t seed, uint32_t layer,
+                                                               float* __restrict__ out, int accumulate) {
+  __shared__ float fac[MAX_FUSED_CLIP_B];
+  clip_factors_to_lds(partials, tiles, C, B, fac, out_norms);
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += stride)
+    aggregate16_one<DT>(scratch, fac, B, S, v, noise_scale, seed, layer, out, accumulate);
 }
 
 template <int DT>

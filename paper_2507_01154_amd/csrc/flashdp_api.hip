@@ -497,7 +497,7 @@ int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mo
     if (stages & FLASHDP_STAGE_CLIP) {
       hipLaunchKernelGGL(explicit_norm_kernel, dim3((unsigned)chunks, (unsigned)B), dim3(256), 0, st, G, S, chunks, a.partials);   // stage 2
       HIP_TRY(hipGetLastError());
-      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, chunks, L.C, factors, L.out_norms);
+      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, st, a.partials, chunks, L.C, (int)B, factors, L.out_norms);
       HIP_TRY(hipGetLastError());
       hipLaunchKernelGGL(explicit_clip_kernel, dim3((unsigned)((S / 4 + 256) / 256), (unsigned)B), dim3(256), 0, st, G, S, factors);  // stage 3
       HIP_TRY(hipGetLastError());
@@ -509,12 +509,26 @@ int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mo
     }
   } else if (use_scratch) {
     if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_SPILL>(plan, dtype, a, st));
-    if (stages & FLASHDP_STAGE_CLIP) {
-      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, tiles, L.C, factors, L.out_norms);
+    // 16-bit scratch in whole 16-byte groups: the inter-block reduce and the clip factors are done by the streaming
+    // kernel itself (one launch less per layer), on a bounded grid so that the factors are not worked out too often
+    const bool fold_clip = dtype != FLASHDP_F32 && S % 8 == 0 && B <= MAX_FUSED_CLIP_B &&
+                           (stages & (FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE)) == (FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE);
+    if (fold_clip) {
+      const size_t n8 = S / 8;
+      const size_t full = (n8 + 255) / 256;
+      const int cus = device_cus();
+      const size_t cap = persistent_grid > 0 ? (size_t)persistent_grid : (size_t)(cus > 0 ? cus : 256) * 8;
+      hipLaunchKernelGGL((clip_aggregate16_kernel<DT_BF16>), dim3((unsigned)std::min(full, cap)), dim3(256), 0, st, a.scratch, a.partials, tiles,
+                         L.C, L.out_norms, (int)B, S, n8, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0);
       HIP_TRY(hipGetLastError());
+    } else {
+      if (stages & FLASHDP_STAGE_CLIP) {
+        hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, st, a.partials, tiles, L.C, (int)B, factors, L.out_norms);
+        HIP_TRY(hipGetLastError());
+      }
+      if (stages & FLASHDP_STAGE_AGGREGATE)
+        HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0, st, persistent_grid));
     }
-    if (stages & FLASHDP_STAGE_AGGREGATE)
-      HIP_TRY(launch_aggregate(dtype, a.scratch, factors, (int)B, S, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0, st, persistent_grid));
   } else {
     int n_partials = tiles;
     if (mode == FLASHDP_SCHEDULE_GHOST) {
@@ -530,7 +544,7 @@ int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mo
       HIP_TRY(launch_gemm<MODE_NORM>(plan, dtype, a, st));
     }
     if (stages & FLASHDP_STAGE_CLIP) {
-      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)B), dim3(256), 0, st, a.partials, n_partials, L.C, factors, L.out_norms);
+      hipLaunchKernelGGL(clip_factors_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, st, a.partials, n_partials, L.C, (int)B, factors, L.out_norms);
       HIP_TRY(hipGetLastError());
     }
     if (stages & FLASHDP_STAGE_AGGREGATE) HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, st));
