@@ -51,8 +51,14 @@ class deferred_weight_grads:
                 r["out"] = torch.empty(r["weight"].shape, dtype=torch.float32, device=r["X"].device)
                 layers.append(dict(X=r["X"], dY=r["dY"], d_in=r["weight"].shape[1], d_out=r["weight"].shape[0], C=r["C"],
                                    sigma=r["sigma"], seed=r["seed"], layer=r["layer"], out_grad=r["out"], out_norms=r["norms"]))
-            F.flashdp_block_dp_grad(layers, B, T, F.dtype_code(recs[0]["X"]), self.schedule)
+            # layers of one group share the noise flag only if they agree; otherwise one call per flag value
+            for flag in sorted({r["add_noise"] for r in recs}, reverse=True):
+                sub = [L for L, r in zip(layers, recs) if r["add_noise"] == flag]
+                F.flashdp_block_dp_grad_micro(sub, B, T, F.dtype_code(recs[0]["X"]), self.schedule, accumulate=False, add_noise=flag)
             for r in recs:
+                if r["module"] is not None and r["module"].keep_fp32_grad:
+                    m = r["module"]
+                    m.grad_fp32 = r["out"].clone() if m.grad_fp32 is None else m.grad_fp32 + r["out"]
                 g = r["out"].to(r["weight"].dtype)
                 r["weight"].grad = g if r["weight"].grad is None else r["weight"].grad + g
         self.pending = []
@@ -60,15 +66,16 @@ class deferred_weight_grads:
 
 class _DPLinearFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, C, sigma, seed, layer, schedule, norms_out):
+    def forward(ctx, x, weight, C, sigma, seed, layer, schedule, norms_out, add_noise, module):
         ctx.save_for_backward(x, weight)
-        ctx.cfg = (float(C), float(sigma), int(seed), int(layer), schedule, norms_out)
+        ctx.cfg = (float(C), float(sigma), int(seed), int(layer), schedule, norms_out, bool(add_noise), module)
         return torch.matmul(x, weight.t())
 
     @staticmethod
     def backward(ctx, dy):
         x, weight = ctx.saved_tensors
-        C, sigma, seed, layer, schedule, norms_out = ctx.cfg
+        C, sigma, seed, layer, schedule, norms_out, add_noise, module = ctx.cfg
+        nothing = (None,) * 8
         d_out, d_in = weight.shape
         B = x.shape[0]
         xs = x.reshape(B, -1, d_in).contiguous()
@@ -81,33 +88,56 @@ class _DPLinearFn(torch.autograd.Function):
         pending = deferred_weight_grads._active
         if pending is not None:   # hand the layer to the per-block call made when the context exits
             pending.pending.append(dict(X=xs, dY=dys, B=B, T=T, weight=weight, C=C, sigma=sigma, seed=seed, layer=layer,
-                                        norms=norms))
-            return grad_x, None, None, None, None, None, None, None
+                                        norms=norms, add_noise=add_noise, module=module))
+            return (grad_x, None) + nothing
         grad_w = torch.empty((d_out, d_in), dtype=torch.float32, device=x.device)
         L = [dict(X=xs, dY=dys, d_in=d_in, d_out=d_out, C=C, sigma=sigma, seed=seed, layer=layer,
                   out_grad=grad_w, out_norms=norms)]
-        F.flashdp_block_dp_grad(L, B, T, F.dtype_code(xs), schedule)
-        return grad_x, grad_w.to(weight.dtype), None, None, None, None, None, None
+        F.flashdp_block_dp_grad_micro(L, B, T, F.dtype_code(xs), schedule, accumulate=False, add_noise=add_noise)
+        if module is not None and module.keep_fp32_grad:
+            module.grad_fp32 = grad_w.clone() if module.grad_fp32 is None else module.grad_fp32 + grad_w
+        return (grad_x, grad_w.to(weight.dtype)) + nothing
 
 
 class DPLinear(torch.nn.Module):
-    """y = x W^T (no bias: the paper's path covers linear weights only).  After backward(), weight.grad is
-    sum_i clip(G_i) + sigma*C*z and last_norms holds the per-sample norms.  `step` is folded into the Philox
-    seed so that the noise differs from one optimizer step to the next; the caller advances it."""
+    """y = x W^T (no bias: the paper's path covers linear weights only).  After backward(), weight.grad holds (torch
+    adds across backward calls) sum_i clip(G_i) + sigma*C*z, and last_norms the per-sample norms.
+
+    Noise and steps.  The Philox field is keyed by (seed, step, layer): `step` is folded into the seed, and with
+    auto_step (the default) it advances by itself at every forward pass whose backward adds noise, so that two
+    optimizer steps never receive the same field - the Gaussian mechanism of Algorithm 1 would be void otherwise
+    (the difference of two updates would be noise-free).  last_seed is the seed the last forward pass used.
+    Gradient accumulation over micro-batches (Appendix D.1): set add_noise = False for all micro-batches of a step but
+    the last; every micro-batch is clipped per sample, torch sums the clipped sums in weight.grad, and the noise goes
+    in once, with the last micro-batch (the step then advances once, too).
+    weight.grad has the parameter's dtype; with keep_fp32_grad the unrounded fp32 sum is kept in grad_fp32 as well
+    (the caller clears it with zero_fp32_grad())."""
 
     def __init__(self, d_in: int, d_out: int, C: float = 1.0, sigma: float = 1.0, seed: int = 0, layer: int = 0,
-                 schedule="auto", dtype=torch.bfloat16, device="cuda"):
+                 schedule="auto", dtype=torch.bfloat16, device="cuda", auto_step: bool = True, keep_fp32_grad: bool = False):
         super().__init__()
         self.weight = torch.nn.Parameter(torch.empty(d_out, d_in, dtype=dtype, device=device))
         torch.nn.init.normal_(self.weight, std=d_in ** -0.5)
         self.C, self.sigma, self.seed, self.layer, self.schedule = C, sigma, seed, layer, schedule
         self.step = 0
+        self.auto_step = auto_step
+        self.add_noise = True
+        self.keep_fp32_grad = keep_fp32_grad
+        self.grad_fp32 = None
         self.last_norms = None
+        self.last_seed = None
 
     def noise_seed(self) -> int:
         return (self.seed + (self.step << 32)) & 0xFFFFFFFFFFFFFFFF
 
+    def zero_fp32_grad(self):
+        self.grad_fp32 = None
+
     def forward(self, x):
         self.last_norms = torch.empty((x.shape[0],), dtype=torch.float32, device=x.device)
-        return _DPLinearFn.apply(x, self.weight, self.C, self.sigma, self.noise_seed(), self.layer, self.schedule,
-                                 self.last_norms)
+        self.last_seed = self.noise_seed()
+        y = _DPLinearFn.apply(x, self.weight, self.C, self.sigma, self.last_seed, self.layer, self.schedule,
+                              self.last_norms, self.add_noise, self)
+        if self.auto_step and self.add_noise and torch.is_grad_enabled():
+            self.step += 1
+        return y

@@ -38,8 +38,9 @@ def test_two_layer_mlp_backward_matches_oracle():
     torch.cuda.synchronize()
     cases = [(l1, x, a1.grad, d0, d1), (l2, torch.relu(a1).detach(), y2.grad, d1, d2)]
     for lin, X, dY, di, do in cases:
-        sig, wn = O.linear_dp_grad(_bits(X), _bits(dY), lin.C, 0.0, lin.noise_seed(), lin.layer)
-        z = O.noise_field(lin.noise_seed(), lin.layer, do * di).reshape(do, di)
+        assert lin.last_seed == (3 + (7 << 32)) and lin.step == 8          # the step advanced by itself
+        sig, wn = O.linear_dp_grad(_bits(X), _bits(dY), lin.C, 0.0, lin.last_seed, lin.layer)
+        z = O.noise_field(lin.last_seed, lin.layer, do * di).reshape(do, di)
         want = sig + lin.sigma * lin.C * z
         got = lin.weight.grad.float().cpu().numpy()
         # weight.grad is rounded to the parameter dtype (bf16): 2^-9 relative per element
@@ -50,6 +51,49 @@ def test_two_layer_mlp_backward_matches_oracle():
     assert l1.noise_seed() != DPLinear(d0, d1, seed=3, device=DEV).noise_seed()
 
 
+def test_steps_advance_and_micro_batches_get_noise_once():
+    """Two backward passes on the same data differ by exactly the difference of two noise fields (the step advanced);
+    three micro-batches with add_noise on the last only sum to the oracle's accumulated gradient with noise added once,
+    in fp32 (keep_fp32_grad)."""
+    from paper_2507_01154_amd.autograd import DPLinear
+    torch.manual_seed(3)
+    B, T, di, do = 6, 40, 72, 136
+    lin = DPLinear(di, do, C=0.05, sigma=0.5, seed=11, layer=2, device=DEV, keep_fp32_grad=True)
+    x = torch.randn(B, T, di, device=DEV).bfloat16()
+    tgt = torch.randn(B, T, do, device=DEV).bfloat16()
+
+    def run(xs, ts):
+        y = lin(xs)
+        y.retain_grad()
+        (((y.float() - ts.float()) ** 2).sum()).backward()
+        return y.grad
+
+    dy = run(x, tgt)
+    g0, s0 = lin.grad_fp32.cpu().numpy().astype(np.float64), lin.last_seed
+    lin.zero_fp32_grad()
+    run(x, tgt)
+    g1, s1 = lin.grad_fp32.cpu().numpy().astype(np.float64), lin.last_seed
+    assert s1 == s0 + (1 << 32) and lin.step == 2
+    z0 = O.noise_field(s0, 2, do * di).reshape(do, di)
+    z1 = O.noise_field(s1, 2, do * di).reshape(do, di)
+    assert np.max(np.abs((g1 - g0) - 0.5 * 0.05 * (z1 - z0))) <= 1e-6          # same clipped sum, two different fields
+    # micro-batches 2 + 3 + 1 of the same batch: noise once, with the last; one step consumed
+    lin.zero_fp32_grad()
+    lin.weight.grad = None
+    splits = [(0, 2), (2, 5), (5, 6)]
+    for k, (a, b) in enumerate(splits):
+        lin.add_noise = k == len(splits) - 1
+        run(x[a:b], tgt[a:b])
+    lin.add_noise = True
+    assert lin.step == 3
+    mbs = [(_bits(x[a:b]), _bits(dy[a:b])) for a, b in splits]
+    want, _ = O.accumulated_dp_grad(mbs, 0.05, 0.5, lin.last_seed, 2)
+    sig, _ = O.accumulated_dp_grad(mbs, 0.05, 0.0, lin.last_seed, 2)
+    z = O.noise_field(lin.last_seed, 2, do * di).reshape(do, di)
+    got = lin.grad_fp32.cpu().numpy().astype(np.float64)
+    assert rel_fro(got - 0.5 * 0.05 * z, sig) <= 4e-3 + 1e-4 and rel_fro(got, want) <= 1e-2
+
+
 def test_deferred_block_call_gives_the_same_gradients():
     """Inside deferred_weight_grads the layers of one backward pass go to the library in a single per-block call
     (overlapped schedule when the shapes allow); the gradients are the ones the layer-by-layer calls produce."""
@@ -57,8 +101,9 @@ def test_deferred_block_call_gives_the_same_gradients():
     import paper_2507_01154_amd as F
     torch.manual_seed(1)
     B, T, d0, d1, d2 = 4, 64, 1024, 1536, 1024
-    l1 = DPLinear(d0, d1, C=0.05, sigma=0.5, seed=5, layer=0, device=DEV)
-    l2 = DPLinear(d1, d2, C=0.05, sigma=0.5, seed=5, layer=1, device=DEV)
+    # auto_step off: the passes below are compared bit for bit, so they must draw the same noise field
+    l1 = DPLinear(d0, d1, C=0.05, sigma=0.5, seed=5, layer=0, device=DEV, auto_step=False)
+    l2 = DPLinear(d1, d2, C=0.05, sigma=0.5, seed=5, layer=1, device=DEV, auto_step=False)
     x = torch.randn(B, T, d0, device=DEV).bfloat16()
     target = torch.randn(B, T, d2, device=DEV).bfloat16()
 
