@@ -56,6 +56,9 @@ def parse():
                     help="secondary variant: q/k/v (and gate/up) read the same X tensor, as in a real decoder block; "
                          "the default gives every layer its own tensors, as the workload states")
     ap.add_argument("--no-comparators", action="store_true")
+    ap.add_argument("--timeline", action="store_true",
+                    help="also run the traced instantiation of the contraction kernel on the workload's largest layer (its data, "
+                         "then all-zero operands) and report where a workgroup's time goes and the clock it ran at")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy: a kernel of known traffic to scale profiler byte counters by")
     return ap.parse_args()
@@ -124,6 +127,50 @@ def mfma_only(F, torch, dev):
         ms = time_events(lambda: F.flashdp_mfma_probe(pattern, iters, wgs, sink), 3, 2)
         out[name + "_tflops"] = round(flop / ms / 1e9, 1)
     return out
+
+
+def contraction_timeline(F, torch, X, dY, B, T, P, D, park, reps=8):
+    """Per-workgroup timeline of the contraction kernel (flashdp_contraction_timeline), summarised: mean microseconds per
+    phase, main-loop shader cycles per k-tile (1024 = matrix cores never idle), the clock the main loop ran at, the gap
+    between two workgroups on a CU, and the share of a CU's time that is not main loop."""
+    import numpy as np
+    L = [dict(X=X, dY=dY, d_in=P, d_out=D, C=1.0, sigma=0.0, seed=0, layer=0, out_grad=None)]
+    ws = torch.empty(F.flashdp_workspace_bytes(L, B, T, F.BF16, "scratch"), dtype=torch.uint8, device=X.device)
+    tiles = ((D + 255) // 256) * ((P + 255) // 256)
+    n = 8 * ((B * ((tiles + 31) // 32) + 7) // 8) * 32
+    trace = torch.zeros(8 * n, dtype=torch.int64, device=X.device)
+    for _ in range(reps):      # the last repetition is the one read: clocks have settled by then
+        trace.zero_()
+        F.flashdp_contraction_timeline(X, dY, B, T, P, D, park, ws, trace)
+    torch.cuda.synchronize()
+    t = trace.cpu().numpy().reshape(-1, 8)
+    t = t[t[:, 7] == 1]
+    us = 0.01
+    st, first, loop, issued, end = [t[:, k].astype(np.float64) * us for k in range(5)]
+    cyc = t[:, 6].astype(np.float64)
+    nk = (T + 31) // 32
+    key = ((t[:, 5] >> 32) << 8) | ((t[:, 5] & 0xFFFFFFFF) >> 8 & 0xFF)
+    gaps = []
+    for k in np.unique(key):
+        m = key == k
+        o = np.argsort(st[m])
+        s_, e_ = st[m][o], end[m][o]
+        gaps.extend(s_[1:] - e_[:-1])
+    span = end.max() - st.min()
+    gap = float(np.mean(gaps)) if gaps else 0.0
+    whole = float((end - st).mean()) + gap
+    return {
+        "workgroups": int(len(t)), "span_us": round(float(span), 1),
+        "tflops": round(2.0 * B * T * P * D / span / 1e6, 1),
+        "fill_us": round(float((first - st).mean()), 2), "main_loop_us": round(float((loop - first).mean()), 2),
+        "epilogue_until_stores_issued_us": round(float((issued - loop).mean()), 2),
+        "store_drain_us": round(float((end - issued).mean()), 2), "gap_to_next_workgroup_us": round(gap, 2),
+        "not_main_loop_share": round(1.0 - float((loop - first).mean()) / whole, 4),
+        "main_loop_cycles_per_k_tile": round(float(cyc.mean()) / nk, 1),
+        "main_loop_matrix_core_busy": round(1024.0 * nk / float(cyc.mean()), 4),
+        "main_loop_clock_ghz": round(float(cyc.mean()) / float((loop - first).mean()) / 1e3, 3),
+        "last_round_idle_share": round(1.0 - float(np.mean([end[key == k].max() for k in np.unique(key)]) - st.min()) / float(span), 4),
+    }
 
 
 def cpu_baseline(w, target_flop=6e12):
@@ -297,6 +344,21 @@ def main():
                                           max(3, args.steps // 4), 2), 4)
             del ws_o
         result["schedule_ms"] = cmp
+        step()
+        torch.cuda.synchronize()
+
+    if args.timeline and w.dtype == "bf16":
+        big = max(range(len(w.layers)), key=lambda k: w.layers[k].d_in * w.layers[k].d_out)
+        X, dY, _, _ = keep[big]
+        spec = w.layers[big]
+        tl = {"layer": spec.name, "B": w.B, "T": w.T, "d_in": spec.d_in, "d_out": spec.d_out}
+        tl["workload_data_park"] = contraction_timeline(F, torch, X, dY, w.B, w.T, spec.d_in, spec.d_out, True)
+        tl["workload_data_norm_only"] = contraction_timeline(F, torch, X, dY, w.B, w.T, spec.d_in, spec.d_out, False)
+        Xz, dYz = torch.zeros_like(X), torch.zeros_like(dY)
+        tl["zero_operands_park"] = contraction_timeline(F, torch, Xz, dYz, w.B, w.T, spec.d_in, spec.d_out, True)
+        tl["zero_operands_norm_only"] = contraction_timeline(F, torch, Xz, dYz, w.B, w.T, spec.d_in, spec.d_out, False)
+        del Xz, dYz
+        result["timeline"] = tl
         step()
         torch.cuda.synchronize()
 

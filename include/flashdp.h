@@ -244,6 +244,21 @@ int flashdp_set_schedule(int schedule);
  * INVALID_ARGUMENT for other patterns, iters or workgroups <= 0 or absurdly large, or a null sink. */
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream);
 
+/* Measurement aid: one launch of the per-sample contraction kernel for large shapes (bf16, tiles loaded straight into
+ * LDS; park = 0: norm only, 1: norm + the bfloat16 tile parked in the workspace) in an instantiation that also records,
+ * per workgroup, where its time went.  trace[8 * w + k] (device, 64-bit words, zero them beforehand) for workgroup w:
+ *   k = 0..4  constant-rate timestamps, 10 ns units: start; first k-tile landed; end of the main loop; stores issued;
+ *             stores acknowledged
+ *   k = 5     XCD id << 32 | hardware id register (CU: bits 8..15)
+ *   k = 6     shader-clock cycles of the main loop (ceil(T / 32) k-tiles; 1024 per k-tile = matrix cores never idle)
+ *   k = 7     1 if the workgroup had a work item (grid slots beyond the last item write nothing).
+ * Returns the number of workgroups launched (trace_entries must be at least that: B * ceil(tiles / 32) * 32 rounded up
+ * to a multiple of 256), or a negative status.  `workspace` as for the scratch schedule of this layer.  d_in, d_out
+ * multiples of 8.  Results of the contraction itself are discarded. */
+int64_t flashdp_contraction_timeline(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                     int park, void* workspace, size_t workspace_bytes, uint64_t* trace, int64_t trace_entries,
+                                     void* stream);
+
 /* Measurement aid: which stages of Algorithm 1 the following calls on this thread enqueue (default: all).
  * With a partial mask the outputs are not meaningful; the stages left out read whatever the workspace
  * holds from an earlier full call.  CONTRACT = per-sample contraction + intra-block norm (the dominant

@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.flashdp_noise_field.restype = ci
         L.flashdp_box_muller.argtypes = [vp, i64, vp, vp]
         L.flashdp_box_muller.restype = ci
+        L.flashdp_contraction_timeline.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, sz, vp, i64, vp]
+        L.flashdp_contraction_timeline.restype = i64
         L.flashdp_mfma_probe.argtypes = [ci, ci, ci, vp, vp]
         L.flashdp_mfma_probe.restype = ci
         L.flashdp_set_stream.argtypes = [vp]
@@ -268,6 +270,16 @@ def flashdp_noise_field(seed: int, layer: int, n: int, z, stream=None):
 
 def flashdp_box_muller(words, n_groups: int, z, stream=None):
     _check(lib().flashdp_box_muller(_ptr(words), n_groups, _ptr(z), _stream_handle(stream)), "flashdp_box_muller")
+
+
+def flashdp_contraction_timeline(X, dY, B: int, T: int, d_in: int, d_out: int, park: bool, workspace, trace, stream=None) -> int:
+    """trace: int64 device tensor of 8 words per workgroup, zeroed; returns the number of workgroups launched."""
+    n = lib().flashdp_contraction_timeline(_ptr(X), _ptr(dY), B, T, d_in, d_out, int(bool(park)), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _ptr(trace), trace.numel() // 8,
+                                           _stream_handle(stream))
+    if n < 0:
+        raise FlashDPError(int(n), "flashdp_contraction_timeline")
+    return int(n)
 
 
 def flashdp_mfma_probe(pattern: int, iters: int, workgroups: int, sink, stream=None):

@@ -483,6 +483,7 @@ int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mo
   a.factors = factors;
   a.out = L.out_grad;
   a.accumulate = accumulate ? 1 : 0;
+  a.trace = nullptr;
   const int tiles = plan.tiles_m * plan.tiles_n;
   const size_t S = (size_t)D * P;
   const float noise_scale = add_noise ? L.sigma * L.C : 0.0f;
@@ -797,7 +798,7 @@ int flashdp_plain_grad(const void* X, const void* dY, int64_t B, int64_t T, int6
   GemmArgs a;
   a.X = X; a.dY = dY; a.B = (int)B; a.T = (int)T; a.P = (int)d_in; a.D = (int)d_out;
   a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
-  a.partials = nullptr; a.scratch = nullptr; a.factors = nullptr; a.out = out_grad; a.accumulate = 0;
+  a.partials = nullptr; a.scratch = nullptr; a.factors = nullptr; a.out = out_grad; a.accumulate = 0; a.trace = nullptr;
   HIP_TRY(launch_gemm<MODE_ACCUM>(plan, dtype, a, static_cast<hipStream_t>(stream)));
   return FLASHDP_OK;
 }
@@ -900,6 +901,37 @@ int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void
   }
   HIP_TRY(hipGetLastError());
   return FLASHDP_OK;
+}
+
+int64_t flashdp_contraction_timeline(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
+                                     int park, void* workspace, size_t workspace_bytes, uint64_t* trace, int64_t trace_entries,
+                                     void* stream) {
+  if (!X || !dY || !workspace || !trace) return FLASHDP_INVALID_ARGUMENT;
+  int st = check_dims(B, T, d_in, d_out);
+  if (st != FLASHDP_OK) return st;
+  if (!aligned16(X) || !aligned16(dY) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(trace) & 7u)) return FLASHDP_MISALIGNED;
+  if (d_in % 8 != 0 || d_out % 8 != 0 || (T + 320) * (d_in > d_out ? d_in : d_out) * 2 >= (int64_t(1) << 31)) return FLASHDP_UNSUPPORTED_SHAPE;
+  int dev = 0;
+  st = device_or_error(&dev);
+  if (st != FLASHDP_OK) return st;
+  Plan plan = make_plan(B, T, d_in, d_out, FLASHDP_BF16);
+  plan.path = plan.accum_path = PATH_DMA; plan.bm = plan.bn = 256;
+  plan.tiles_m = (int)((d_out + 255) / 256); plan.tiles_n = (int)((d_in + 255) / 256);
+  const WsLayout wl = ws_layout(plan, B, T, d_in, d_out, FLASHDP_BF16, park ? FLASHDP_SCHEDULE_SCRATCH : FLASHDP_SCHEDULE_TWOPASS);
+  if (workspace_bytes < wl.total) return FLASHDP_WORKSPACE_TOO_SMALL;
+  GemmArgs a;
+  a.X = X; a.dY = dY; a.B = (int)B; a.T = (int)T; a.P = (int)d_in; a.D = (int)d_out;
+  a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
+  char* ws = static_cast<char*>(workspace);
+  a.partials = reinterpret_cast<float*>(ws + wl.partials);
+  a.scratch = park ? (void*)(ws + wl.scratch) : nullptr;
+  a.factors = nullptr; a.out = nullptr; a.accumulate = 0;
+  a.trace = reinterpret_cast<unsigned long long*>(trace);
+  const int64_t grid = shared_block_grid(plan.tiles_m * plan.tiles_n, (int)B);
+  if (trace_entries < grid) return FLASHDP_WORKSPACE_TOO_SMALL;
+  if (park) HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE_SPILL, DT_BF16, true>, MODE_SPILL, a, static_cast<hipStream_t>(stream), true));
+  else HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE_NORM, DT_BF16, true>, MODE_NORM, a, static_cast<hipStream_t>(stream), true));
+  return grid;
 }
 
 int flashdp_set_stream(void* hip_stream) { g_ctx.stream = static_cast<hipStream_t>(hip_stream); return FLASHDP_OK; }

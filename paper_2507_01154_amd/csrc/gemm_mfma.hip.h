@@ -79,6 +79,7 @@ struct GemmArgs {
   const float* factors;  // [B] clip factors (ACCUM); nullptr = all ones
   float* out;            // [D][P] (ACCUM)
   int accumulate;        // ACCUM: add to what out holds (gradient accumulation over micro-batches) instead of overwriting
+  unsigned long long* trace;   // measurement aid (traced instantiation of the direct-to-LDS kernel only): 8 words per workgroup
 };
 
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int WAVES_PER_EU_ = 0>

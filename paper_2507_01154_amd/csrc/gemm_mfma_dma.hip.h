@@ -69,11 +69,17 @@ __device__ __forceinline__ void wait_loads_outstanding() {
   if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
 }
 
-template <typename Cfg, int MODE, int DT>
+// TRACE (measurement aid, off in every instantiation the library computes with): the workgroup also records where
+// its time goes - constant-rate timestamps (100 MHz) at its start, when its first k-tile has landed, at the end of
+// the main loop, when the epilogue has issued its stores and when they are acknowledged; the shader-clock cycles the
+// main loop took (so that the clock the part actually ran at can be read off); and which XCD / CU it ran on.
+template <typename Cfg, int MODE, int DT, bool TRACE = false>
 __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kernel(const GemmArgs a) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, FM = Cfg::FM, FN = Cfg::FN, STAGES = Cfg::STAGES;
   constexpr int ROW = 256;   // elements per LDS row of either operand (BM == BN == 256)
   extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+  unsigned long long t_start = 0, t_first = 0, t_loop = 0, t_issued = 0, c_first = 0, c_loop = 0;
+  if constexpr (TRACE) t_start = __builtin_amdgcn_s_memrealtime();
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -162,6 +168,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kern
   for (int s = 0; s < STAGES - 1; ++s) issue_loads(s);
   wait_loads_outstanding<4 * (STAGES - 2)>();   // k-tile 0 has landed
   __syncthreads();
+  if constexpr (TRACE) { t_first = __builtin_amdgcn_s_memrealtime(); c_first = __builtin_amdgcn_s_memtime(); }
   load_frags(0, 0, fa[0], fb[0]);
 
   constexpr int N_MMA = FM * FN, N_RD = 2 * (FM + FN);
@@ -207,8 +214,24 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_dma_kern
   }
   wait_loads_outstanding<0>();   // parked loads still write (zeros) into LDS: let them finish before LDS is reused
   __syncthreads();
+  if constexpr (TRACE) { t_loop = __builtin_amdgcn_s_memrealtime(); c_loop = __builtin_amdgcn_s_memtime(); }
 
   tile_epilogue<Cfg, MODE, DT>(a, acc, lds, m0, n0, sample0, tile, tiles);
+  if constexpr (TRACE) {
+    t_issued = __builtin_amdgcn_s_memrealtime();
+    wait_loads_outstanding<0>();
+    const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
+    if (tid == 0) {
+      uint32_t hw_id, xcc_id;
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_id));
+      unsigned long long* p = a.trace + (size_t)blockIdx.x * 8;
+      p[0] = t_start; p[1] = t_first; p[2] = t_loop; p[3] = t_issued; p[4] = t_end;
+      p[5] = ((unsigned long long)(xcc_id & 0xFu) << 32) | hw_id;
+      p[6] = c_loop - c_first;
+      p[7] = 1;   // entry written (workgroups beyond the last work item write nothing)
+    }
+  }
 }
 
 }  // namespace flashdp

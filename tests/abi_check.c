@@ -9,7 +9,7 @@ int main(void) {
   typedef void (*fn_t)(void);
   fn_t syms[] = {
       (fn_t)flashdp_linear_dp_grad, (fn_t)flashdp_block_dp_grad, (fn_t)flashdp_block_dp_grad_micro,
-      (fn_t)flashdp_workspace_bytes, (fn_t)flashdp_workspace_bytes_chunked, (fn_t)flashdp_last_chunk, (fn_t)flashdp_linear_dp_grad_static, (fn_t)flashdp_static_scratch_bytes, (fn_t)flashdp_plain_grad, (fn_t)flashdp_plain_grad_balanced, (fn_t)flashdp_plain_grad_balanced_workspace_bytes, (fn_t)flashdp_noise_field, (fn_t)flashdp_box_muller, (fn_t)flashdp_mfma_probe,
+      (fn_t)flashdp_workspace_bytes, (fn_t)flashdp_workspace_bytes_chunked, (fn_t)flashdp_last_chunk, (fn_t)flashdp_linear_dp_grad_static, (fn_t)flashdp_static_scratch_bytes, (fn_t)flashdp_plain_grad, (fn_t)flashdp_plain_grad_balanced, (fn_t)flashdp_plain_grad_balanced_workspace_bytes, (fn_t)flashdp_noise_field, (fn_t)flashdp_box_muller, (fn_t)flashdp_mfma_probe, (fn_t)flashdp_contraction_timeline,
       (fn_t)flashdp_set_stream, (fn_t)flashdp_set_workspace, (fn_t)flashdp_set_dtype, (fn_t)flashdp_set_layer,
       (fn_t)flashdp_set_schedule, (fn_t)flashdp_set_stages, (fn_t)flashdp_release, (fn_t)flashdp_last_schedule, (fn_t)flashdp_last_kernel,
       (fn_t)flashdp_status_string, (fn_t)flashdp_version};

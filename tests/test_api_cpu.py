@@ -141,7 +141,7 @@ def test_register_budget_of_the_overlapped_schedule():
         if m and cur:
             usage[cur][m.group(1)] = int(m.group(2))
     up8 = lambda n: (n + 7) // 8 * 8
-    spill = [k for k in usage if "gemm_mfma_dma_kernel" in k and "ELi1ELi" in k]          # MODE_SPILL, bf16 and f16
+    spill = [k for k in usage if "gemm_mfma_dma_kernel" in k and "ELi1ELi" in k and k.endswith("Lb0EEEvNS_8GemmArgsE")]   # MODE_SPILL, bf16 and f16, untraced
     agg = [k for k in usage if "aggregate16_persistent_kernel" in k]
     assert len(spill) == 2 and len(agg) == 1
     for k in spill:

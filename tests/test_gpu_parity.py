@@ -680,3 +680,25 @@ def test_fused_schedule_falls_back_where_it_does_not_apply():
     assert F.flashdp_workspace_bytes(L, 8, 2048, F.BF16, "fused") == F.flashdp_workspace_bytes(L, 8, 2048, F.BF16, "scratch")
     L = [dict(X=None, dY=None, d_in=4096, d_out=4096, C=1.0, sigma=1.0, seed=0, layer=0, out_grad=None)]
     assert F.flashdp_workspace_bytes(L, 4, 2048, F.BF16, "fused") < 0.8 * F.flashdp_workspace_bytes(L, 4, 2048, F.BF16, "scratch")   # one sample is never parked
+
+
+def test_contraction_timeline_measurement_aid():
+    B, T, P, D = 3, 256, 1160, 1320          # 30 tiles of 256 x 256 per sample, ragged
+    w = W.scaled_down(W.WORKLOADS["gpt2_small_mlp_up"], B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    dX, ddY = to_device(X), to_device(dY)
+    L = [dict(X=None, dY=None, d_in=P, d_out=D, C=1.0, sigma=0.0, seed=0, layer=0, out_grad=None)]
+    ws = torch.empty(F.flashdp_workspace_bytes(L, B, T, F.BF16, "scratch"), dtype=torch.uint8, device=DEV)
+    for park in (False, True):
+        trace = torch.zeros(8 * 256, dtype=torch.int64, device=DEV)
+        n = F.flashdp_contraction_timeline(dX, ddY, B, T, P, D, park, ws, trace)
+        torch.cuda.synchronize()
+        t = trace.cpu().numpy().reshape(-1, 8)
+        assert n == 256 and int(t[:, 7].sum()) == B * 30            # one entry per (sample, tile), none for the empty grid slots
+        t = t[t[:, 7] == 1]
+        assert np.all(t[:, 0] <= t[:, 1]) and np.all(t[:, 1] < t[:, 2]) and np.all(t[:, 2] <= t[:, 3]) and np.all(t[:, 3] <= t[:, 4])
+        assert np.all(t[:, 6] >= 1024 * (T // 32)) and np.all(t[:, 6] < 100 * 1024 * (T // 32))   # the matrix cores cannot be busier than always
+        assert np.all((t[:, 5] >> 32) < 8)
+    with pytest.raises(F.FlashDPError) as ei:
+        F.flashdp_contraction_timeline(dX, ddY, B, T, P, D, True, ws, torch.zeros(8 * 64, dtype=torch.int64, device=DEV))
+    assert ei.value.status == F.WORKSPACE_TOO_SMALL
