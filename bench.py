@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama13b_block")
-    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch", "explicit", "overlap", "ghost"])
+    ap.add_argument("--schedule", default="auto", choices=["auto", "twopass", "scratch", "explicit", "overlap", "ghost", "fused"])
     ap.add_argument("--no-schedule-comparison", action="store_true",
                     help="skip timing the other schedules (two-pass recompute, explicit four-stage) beside the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -237,7 +237,7 @@ def main():
     sched = args.schedule
     ws = None
     if sched != "twopass":
-        ws_kind = {"explicit": "explicit", "scratch": "scratch", "ghost": "ghost"}.get(sched, "overlap")
+        ws_kind = {"explicit": "explicit", "scratch": "scratch", "ghost": "ghost", "fused": "fused"}.get(sched, "overlap")
         ws = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, ws_kind), dtype=torch.uint8, device=dev)
 
     def step():
@@ -251,20 +251,24 @@ def main():
     ms_median, ms_min = time_each(step, args.steps, 2)   # spread of single steps, outside the timed region above
 
     # dominant kernel alone (the per-sample contraction + intra-block norm), same launches, same stream
-    F.flashdp_set_stages(F.STAGE_CONTRACT)
-    ms_contract = time_events(step, args.steps, 2)
-    F.flashdp_set_stages(F.STAGE_AGGREGATE)
-    ms_aggregate = time_events(step, args.steps, 2)
-    F.flashdp_set_stages(F.STAGE_ALL)
-    step()
-    torch.cuda.synchronize()
+    if used == "fused":      # one kernel does everything: there are no stages to time apart
+        ms_contract, ms_aggregate = time_events(step, args.steps, 2), 0.0
+    else:
+        F.flashdp_set_stages(F.STAGE_CONTRACT)
+        ms_contract = time_events(step, args.steps, 2)
+        F.flashdp_set_stages(F.STAGE_AGGREGATE)
+        ms_aggregate = time_events(step, args.steps, 2)
+        F.flashdp_set_stages(F.STAGE_ALL)
+        step()
+        torch.cuda.synchronize()
     hw_flops = flops * (2.0 if used == "twopass" else 1.0)
     if used == "ghost":   # upper-triangular blocks of both T x T Gram matrices, then the gradient itself
         hw_flops = flops + sum(float(w.B) * w.T * (w.T + 128) * (s.d_in + s.d_out) for s in w.layers)
     traffic_key = "scratch" if used == "overlap" else used
     n_launch = len(w.layers)
     what = {"scratch": "per-sample contraction + norm + spill", "twopass": "per-sample contraction + norm (first of two passes)",
-            "explicit": "per-sample contraction, fp32 gradients materialised", "ghost": "Gram-matrix norms"}[traffic_key]
+            "explicit": "per-sample contraction, fp32 gradients materialised", "ghost": "Gram-matrix norms",
+            "fused": "the whole of Algorithm 1 in one launch"}[traffic_key]
     roofline = {
         "bound": "mfma", "kernel": f"{'gram_norm_mfma_kernel' if used == 'ghost' else kernel} ({what})",
         "achieved": round(flops / ms_contract / 1e9, 2), "peak": peak, "unit": "TFLOP/s",
@@ -336,7 +340,7 @@ def main():
         # explicit four-stage flow with materialised fp32 per-sample gradients (its "explicit" class), and the
         # ghost-norm route (norms from T x T Gram matrices, then one clipped accumulation)
         cmp = {used: round(ms, 4)}
-        for other in ("overlap", "scratch", "twopass", "explicit", "ghost"):
+        for other in ("overlap", "scratch", "twopass", "explicit", "ghost", "fused"):
             if other in cmp:
                 continue
             ws_o = torch.empty(F.flashdp_workspace_bytes(arr, w.B, w.T, dtype_code, other), dtype=torch.uint8, device=dev)

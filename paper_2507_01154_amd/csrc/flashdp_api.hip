@@ -511,16 +511,19 @@ int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mo
   } else if (use_scratch) {
     if (stages & FLASHDP_STAGE_CONTRACT) HIP_TRY(launch_gemm<MODE_SPILL>(plan, dtype, a, st));
     // 16-bit scratch in whole 16-byte groups: the inter-block reduce and the clip factors are done by the streaming
-    // kernel itself (one launch less per layer), on a bounded grid so that the factors are not worked out too often
+    // kernel itself (one launch less per layer) when that is cheap: every workgroup reads all B * tiles partials, so
+    // with the ordinary grid (one workgroup per 2048 elements) this is only done while those redundant reads stay
+    // below 64 MB (a 4096 x 4096 layer: 32 MB; the Llama-13B layers would re-read 0.16-1.2 GB, and a grid bounded
+    // to avoid that streams measurably slower: 191 vs 153 + 7 us per layer); the bounded grid of the overlapped
+    // schedule always qualifies.
+    const size_t n8_all = S / 8, full_grid = (n8_all + 255) / 256;
+    const size_t agg_grid = persistent_grid > 0 ? std::min((size_t)persistent_grid, full_grid) : full_grid;
     const bool fold_clip = dtype != FLASHDP_F32 && S % 8 == 0 && B <= MAX_FUSED_CLIP_B &&
+                           agg_grid * (size_t)B * tiles * 4 <= (size_t(64) << 20) &&
                            (stages & (FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE)) == (FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE);
     if (fold_clip) {
-      const size_t n8 = S / 8;
-      const size_t full = (n8 + 255) / 256;
-      const int cus = device_cus();
-      const size_t cap = persistent_grid > 0 ? (size_t)persistent_grid : (size_t)(cus > 0 ? cus : 256) * 8;
-      hipLaunchKernelGGL((clip_aggregate16_kernel<DT_BF16>), dim3((unsigned)std::min(full, cap)), dim3(256), 0, st, a.scratch, a.partials, tiles,
-                         L.C, L.out_norms, (int)B, S, n8, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0);
+      hipLaunchKernelGGL((clip_aggregate16_kernel<DT_BF16>), dim3((unsigned)agg_grid), dim3(256), 0, st, a.scratch, a.partials, tiles,
+                         L.C, L.out_norms, (int)B, S, n8_all, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0);
       HIP_TRY(hipGetLastError());
     } else {
       if (stages & FLASHDP_STAGE_CLIP) {
