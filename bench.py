@@ -42,6 +42,49 @@ def measured_traffic(workload, schedule, kernel):
     return None
 
 
+def write_traffic(fetch_dir, write_dir, workload, schedule, kernel):
+    """Reads the p_counter_collection.csv of two rocprofv3 --pmc runs of this script (FETCH_SIZE in one, WRITE_SIZE in
+    the other, both with --copy-probe) and records, in profiles/traffic.json, the average HBM-side bytes per launch of
+    `kernel` (a substring of the profiler's kernel name), scaled by what the same counter read for the 1 GiB copy of
+    --copy-probe.  No GPU needed."""
+    import csv
+    import datetime
+    import subprocess
+
+    def read(d, counter):
+        rows = [r for r in csv.DictReader(open(os.path.join(d, "p_counter_collection.csv"))) if r["Counter_Name"] == counter]
+        copies = [float(r["Counter_Value"]) for r in rows if "copyBuffer" in r["Kernel_Name"]]
+        mine = [float(r["Counter_Value"]) for r in rows if kernel in r["Kernel_Name"]]
+        if not copies or not mine:
+            raise SystemExit(f"{d}: no {counter} rows for the copy probe or for a kernel named like {kernel!r}")
+        scale = float(1 << 20) / max(copies)          # KiB the 1 GiB copy moved each way / KiB the counter read
+        return sum(mine) / len(mine) * 1024.0 * scale, scale, len(mine)
+
+    rd, rscale, n_r = read(fetch_dir, "FETCH_SIZE")
+    wr, wscale, n_w = read(write_dir, "WRITE_SIZE")
+    try:
+        commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True, text=True).stdout.strip()
+    except OSError:
+        commit = ""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        table = {"entries": []}
+    name = "gemm_mfma_dma_kernel" if "gemm_mfma_dma_kernel" in kernel else kernel
+    entry = {"workload": workload, "schedule": schedule, "kernel": name, "profiler_kernel_match": kernel,
+             "read_bytes": round(rd), "write_bytes": round(wr), "fetch_size_scale": round(rscale, 4), "write_size_scale": round(wscale, 4),
+             "dispatches_averaged": [n_r, n_w], "commit": commit, "date": datetime.date.today().isoformat(),
+             "command": "rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE -d <dir> -o p --output-format csv -- python3 bench.py --steps 3 --warmup 1 "
+                        f"--no-cpu-baseline --no-comparators --no-schedule-comparison --copy-probe --workload {workload} --schedule {schedule}"}
+    table["entries"] = [e for e in table.get("entries", []) if not (e.get("workload") == workload and e.get("schedule") == schedule and e.get("kernel") == name)]
+    table["entries"].append(entry)
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(table, f, indent=1)
+        f.write("\n")
+    print(json.dumps(entry))
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +102,11 @@ def parse():
     ap.add_argument("--timeline", action="store_true",
                     help="also run the traced instantiation of the contraction kernel on the workload's largest layer (its data, "
                          "then all-zero operands) and report where a workgroup's time goes and the clock it ran at")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no benchmark: read two rocprofv3 --pmc output folders (FETCH_SIZE, WRITE_SIZE runs of this script with "
+                         "--copy-probe) and record the dominant kernel's measured bytes per launch in profiles/traffic.json")
+    ap.add_argument("--traffic-kernel", default="gemm_mfma_dma_kernel<flashdp::DmaCfg<4>, 1,",
+                    help="substring of the profiler's kernel name to average over (default: the contraction kernel in its parking mode)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy: a kernel of known traffic to scale profiler byte counters by")
     return ap.parse_args()
@@ -205,6 +253,10 @@ def cpu_baseline(w, target_flop=6e12):
 
 def main():
     args = parse()
+    if args.traffic_from:
+        write_traffic(args.traffic_from[0], args.traffic_from[1], args.workload, "scratch" if args.schedule in ("auto", "overlap") else args.schedule,
+                      args.traffic_kernel)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
