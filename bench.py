@@ -107,6 +107,9 @@ def parse():
                          "--copy-probe) and record the dominant kernel's measured bytes per launch in profiles/traffic.json")
     ap.add_argument("--traffic-kernel", default="gemm_mfma_dma_kernel<flashdp::DmaCfg<4>, 1,",
                     help="substring of the profiler's kernel name to average over (default: the contraction kernel in its parking mode)")
+    ap.add_argument("--vendor-envelope", action="store_true",
+                    help="also time the vendor GEMM (torch.matmul) on 8192^3 bf16 in its best layout (reduction index contiguous for both "
+                         "operands) and in this path's layout (reduction index slowest for both), on N(0,1) data and on zeros")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy: a kernel of known traffic to scale profiler byte counters by")
     return ap.parse_args()
@@ -171,7 +174,8 @@ def mfma_only(F, torch, dev):
     wgs, iters = 1024, 20000
     flop = wgs * 8 * iters * 16 * 32768.0
     out = {}
-    for name, pattern in (("zeros", 0), ("random", 1), ("lds_zeros", 2), ("lds_random", 3)):
+    for name, pattern in (("zeros", 0), ("random", 1), ("lds_zeros", 2), ("lds_random", 3), ("random_shared_operand_order", 4),
+                          ("random_one_operand_pair", 5), ("random_wide_exponents", 6)):
         ms = time_events(lambda: F.flashdp_mfma_probe(pattern, iters, wgs, sink), 3, 2)
         out[name + "_tflops"] = round(flop / ms / 1e9, 1)
     return out
@@ -417,6 +421,18 @@ def main():
         result["timeline"] = tl
         step()
         torch.cuda.synchronize()
+
+    if args.vendor_envelope:
+        env = {}
+        n = 8192
+        for kind in ("randn", "zeros"):
+            mk = (lambda *sh: torch.randn(*sh, device=dev).bfloat16()) if kind == "randn" else (lambda *sh: torch.zeros(*sh, device=dev, dtype=torch.bfloat16))
+            a_mk, b_nk, a_km, b_kn = mk(n, n), mk(n, n), mk(n, n), mk(n, n)
+            t_best = time_events(lambda: torch.matmul(a_mk, b_nk.t()), 10, 3)
+            t_ours = time_events(lambda: torch.matmul(a_km.t(), b_kn), 10, 3)
+            env[kind] = {"k_contiguous_tflops": round(2.0 * n ** 3 / t_best / 1e9, 1), "k_slowest_tflops": round(2.0 * n ** 3 / t_ours / 1e9, 1)}
+            del a_mk, b_nk, a_km, b_kn
+        result["vendor_gemm_8192_cubed"] = env
 
     if args.copy_probe:
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

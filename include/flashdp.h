@@ -239,7 +239,10 @@ int flashdp_set_schedule(int schedule);
  * no barrier - so that a benchmark can quote the rate this part actually sustains next to the nominal peak.
  * pattern 0 = all-zero operands, 1 = pseudo-random operands, both held in registers; 2 and 3 = the same two
  * with the operand fragments re-read from LDS every k-step through the contraction kernel's transposed reads
- * (matrix cores + LDS traffic, still no memory loads and no barrier).  `workgroups` workgroups of 8 waves, each
+ * (matrix cores + LDS traffic, still no memory loads and no barrier); 4 = the random operands of 1 with consecutive
+ * instructions of a wave sharing one operand fragment, 5 = with one and the same operand pair for every instruction,
+ * 6 = random operands with eight different exponents instead of two (4-6: does the rate on random data depend on how
+ * operands are delivered, or on the values themselves?).  `workgroups` workgroups of 8 waves, each
  * wave issuing 16 * iters instructions of 32768 FLOP; sink (device, 4 bytes) is never written in practice.
  * INVALID_ARGUMENT for other patterns, iters or workgroups <= 0 or absurdly large, or a null sink. */
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream);

@@ -892,12 +892,12 @@ int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* 
 }
 
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream) {
-  if (pattern < 0 || pattern > 3 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
+  if (pattern < 0 || pattern > 6 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
     return FLASHDP_INVALID_ARGUMENT;
   int dev = 0;
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
-  if (pattern >= 2) {   // 2, 3: zeros / random with the operand fragments re-read from LDS every k-step
+  if (pattern == 2 || pattern == 3) {   // zeros / random with the operand fragments re-read from LDS every k-step
     hipLaunchKernelGGL(mfma_lds_probe_kernel, dim3((unsigned)workgroups), dim3(512), lds_plan::STAGE_ELEMS * 2, static_cast<hipStream_t>(stream), pattern - 2, iters, sink);
   } else {
     hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), pattern, iters, sink);

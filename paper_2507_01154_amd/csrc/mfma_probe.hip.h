@@ -13,7 +13,11 @@
 
 namespace flashdp {
 
-// pattern 0: zeros; 1: pseudo-random bf16 values in (-2, 2) made from a hash of the lane and fragment index
+// pattern 0: zeros; 1: pseudo-random bf16 values in (-2, 2) made from a hash of the lane and fragment index;
+// 4: the values of 1 with the instructions in boustrophedon order (consecutive instructions of a wave share one
+// operand fragment); 5: the values of 1 with one and the same operand pair for every instruction; 6: pseudo-random
+// values with eight different exponents (2^-7 .. 2) instead of two.  4-6 answer whether the rate on random data
+// depends on how operands are delivered or on the values themselves.
 __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int iters, float* __restrict__ sink) {
   const uint32_t gid = blockIdx.x * 512u + threadIdx.x;
   s16x8_t fa[2][4], fb[2][2];
@@ -22,8 +26,9 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
     for (int e = 0; e < 8; ++e) {
       uint32_t h = (gid * 0x9E3779B9u) ^ (salt * 0x85EBCA6Bu) ^ ((uint32_t)e * 0xC2B2AE35u);
       h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 12; h *= 0x297A2D39u; h ^= h >> 15;
-      // sign and 7 mantissa bits from the hash, exponent of 0.5 .. 2
-      const uint32_t bits = (h & 0x8000u) | ((126u + ((h >> 16) % 2u)) << 7) | (h & 0x7Fu);
+      // sign and 7 mantissa bits from the hash, exponent of 0.5 .. 2 (pattern 6: of 2^-7 .. 2)
+      const uint32_t ex = pattern == 6 ? 120u + ((h >> 16) % 8u) : 126u + ((h >> 16) % 2u);
+      const uint32_t bits = (h & 0x8000u) | (ex << 7) | (h & 0x7Fu);
       f[e] = pattern ? (short)bits : (short)0;
     }
   };
@@ -41,13 +46,36 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-  for (int it = 0; it < iters; ++it) {
+  if (pattern == 4) {
+    for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+      for (int s = 0; s < 2; ++s)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT_BF16>(fb[s][j], fa[s][i], acc[i][j]);
+          for (int jj = 0; jj < 2; ++jj) {
+            const int j = (i & 1) ? 1 - jj : jj;
+            acc[i][j] = mfma32<DT_BF16>(fb[s][j], fa[s][i], acc[i][j]);
+          }
+    }
+  } else if (pattern == 5) {
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT_BF16>(fb[0][0], fa[0][0], acc[i][j]);
+    }
+  } else {
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT_BF16>(fb[s][j], fa[s][i], acc[i][j]);
+    }
   }
   float t = 0.0f;
 #pragma unroll
