@@ -834,11 +834,9 @@ int flashdp_plain_grad_balanced(const void* X, const void* dY, int64_t B, int64_
   a.X = X; a.dY = dY; a.B = (int)B; a.T = (int)T; a.P = (int)d_in; a.D = (int)d_out;
   a.tiles_m = (int)((d_out + 255) / 256); a.tiles_n = (int)((d_in + 255) / 256);
   const int tiles = a.tiles_m * a.tiles_n;
-  a.n_blocks = (tiles + STREAMK_WG_PER_XCD - 1) / STREAMK_WG_PER_XCD;
-  const int64_t nk = B * ((T + CfgDma::BK - 1) / CfgDma::BK);
-  const int64_t nk_pad = (nk + CfgDma::STAGES - 1) / CfgDma::STAGES * CfgDma::STAGES;
-  const int64_t total = (int64_t)a.n_blocks * nk_pad;
-  const int64_t per = ((total + STREAMK_XCDS - 1) / STREAMK_XCDS + CfgDma::STAGES - 1) / CfgDma::STAGES * CfgDma::STAGES;
+  long n_blocks = 0, nk_pad = 0, per = 0;
+  streamk_sizes((long)B, (long)T, (long)tiles, CfgDma::BK, CfgDma::STAGES, &n_blocks, &nk_pad, &per);
+  a.n_blocks = (int)n_blocks;
   if (nk_pad >= (int64_t(1) << 30) || per >= (int64_t(1) << 30)) return FLASHDP_UNSUPPORTED_SHAPE;
   a.nk_pad = (int)nk_pad;
   a.units_per_xcd = (int)per;

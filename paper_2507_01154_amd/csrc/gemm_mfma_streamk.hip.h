@@ -16,13 +16,9 @@
 #include <stdint.h>
 
 #include "gemm_mfma_dma.hip.h"
+#include "streamk_plan.h"
 
 namespace flashdp {
-
-constexpr int STREAMK_XCDS = 8;            // ranges the work is cut into (workgroup id mod 8 = XCD)
-constexpr int STREAMK_WG_PER_XCD = 32;     // = SHARE_BLOCK: one workgroup per tile of a block
-constexpr int STREAMK_SLOTS = 2 * STREAMK_XCDS;   // a range starts and ends with at most one cut block each
-constexpr int STREAMK_MAX_CUT = 16;        // blocks that can be cut (one per range boundary, both sides)
 
 struct StreamKArgs {
   const void* X;        // [B][T][P]
@@ -44,30 +40,6 @@ struct StreamKCuts {
   int count[STREAMK_MAX_CUT];
   int slot[STREAMK_MAX_CUT][STREAMK_XCDS];
 };
-
-// One piece of one range: block, k-range, and the partial slot it is stored to (-1: the whole reduction, store to out).
-struct StreamKPiece { int block, k0, k1, slot; };
-
-// The walk over range `xcd`: calls f(piece) for every piece in order.  Host and device use the same code.
-template <typename F>
-__host__ __device__ __forceinline__ void streamk_walk(int xcd, int n_blocks, int nk_pad, int units_per_xcd, F&& f) {
-  const long total = (long)n_blocks * nk_pad;
-  long u = (long)xcd * units_per_xcd;
-  const long u_end = u + units_per_xcd < total ? u + units_per_xcd : total;
-  int n_partial = 0;
-  while (u < u_end) {
-    StreamKPiece p;
-    p.block = (int)(u / nk_pad);
-    p.k0 = (int)(u - (long)p.block * nk_pad);
-    const long left = u_end - u;
-    p.k1 = p.k0 + left < nk_pad ? (int)(p.k0 + left) : nk_pad;
-    const bool whole = p.k0 == 0 && p.k1 == nk_pad;
-    p.slot = whole ? -1 : 2 * xcd + n_partial;
-    if (!whole) ++n_partial;
-    f(p);
-    u += p.k1 - p.k0;
-  }
-}
 
 template <typename Cfg, int DT>
 __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_streamk_kernel(const StreamKArgs a) {

@@ -15,3 +15,20 @@ int plan_frag_row(int lane) { return frag_row(lane); }
 int plan_frag_col(int lane) { return frag_col(lane); }
 int plan_frag_offset(int lane, int block) { return frag_offset(lane, block); }
 }
+
+// The walk of the balanced non-private gradient (which XCD computes which k-range of which block of tiles).
+#include "../paper_2507_01154_amd/csrc/streamk_plan.h"
+extern "C" {
+void sk_sizes(long B, long T, long tiles, long* n_blocks, long* nk_pad, long* units) { flashdp::streamk_sizes(B, T, tiles, 32, 4, n_blocks, nk_pad, units); }
+// writes up to cap pieces of range xcd as (block, k0, k1, slot) quadruples; returns the number of pieces
+int sk_walk(int xcd, int n_blocks, int nk_pad, int units, int* out, int cap) {
+  int n = 0;
+  flashdp::streamk_walk(xcd, n_blocks, nk_pad, units, [&](const flashdp::StreamKPiece& p) {
+    if (n < cap) { out[4 * n] = p.block; out[4 * n + 1] = p.k0; out[4 * n + 2] = p.k1; out[4 * n + 3] = p.slot; }
+    ++n;
+  });
+  return n;
+}
+int sk_slots() { return flashdp::STREAMK_SLOTS; }
+int sk_max_cut() { return flashdp::STREAMK_MAX_CUT; }
+}

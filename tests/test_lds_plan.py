@@ -110,3 +110,47 @@ def test_transposed_reads_are_bank_conflict_free(plan):
                 byte = 2 * plan.plan_frag_offset(lane, block)
                 banks += [(byte // 4) % 64, (byte // 4 + 1) % 64]
             assert len(set(banks)) == 64
+
+
+# ---- the balanced non-private gradient: which XCD computes which k-range of which block (csrc/streamk_plan.h) ----
+
+SK_SHAPES = [  # B, T, d_in, d_out
+    (8, 2048, 5120, 5120), (8, 2048, 5120, 13824), (8, 2048, 13824, 5120), (4, 2048, 4096, 4096), (8, 1024, 768, 3072),
+    (3, 160, 264, 392), (2, 100, 1544, 2056), (2, 192, 5120, 5120), (1, 33, 264, 24), (1, 1, 8, 8), (5, 31, 8192, 8192),
+    (16, 4096, 256, 256), (2, 64, 16384, 16384),
+]
+
+
+@pytest.mark.parametrize("shape", SK_SHAPES)
+def test_balanced_gradient_walk_covers_every_block_once(plan, shape):
+    B, T, P, D = shape
+    tiles = -(-D // 256) * -(-P // 256)
+    nb, nkp, per = ctypes.c_long(), ctypes.c_long(), ctypes.c_long()
+    plan.sk_sizes(B, T, tiles, ctypes.byref(nb), ctypes.byref(nkp), ctypes.byref(per))
+    nb, nkp, per = nb.value, nkp.value, per.value
+    assert nb == -(-tiles // 32) and nkp % 4 == 0 and nkp >= B * -(-T // 32) and per % 4 == 0 and 8 * per >= nb * nkp
+    cover, cuts, slots = {}, {}, []
+    buf = (ctypes.c_int * (4 * 64))()
+    for x in range(8):
+        n = plan.sk_walk(x, nb, nkp, per, buf, 64)
+        assert n <= 64
+        n_partial = 0
+        for k in range(n):
+            blk, k0, k1, slot = buf[4 * k], buf[4 * k + 1], buf[4 * k + 2], buf[4 * k + 3]
+            assert 0 <= blk < nb and 0 <= k0 < k1 <= nkp and k0 % 4 == 0 and k1 % 4 == 0
+            cover.setdefault(blk, []).append((k0, k1))
+            if slot >= 0:
+                assert slot == 2 * x + n_partial and slot < plan.sk_slots()     # at most two cut pieces per range
+                n_partial += 1
+                cuts.setdefault(blk, []).append(slot)
+                slots.append(slot)
+            else:
+                assert (k0, k1) == (0, nkp)
+    for blk in range(nb):                      # every block's reduction is covered exactly once, in order
+        segs = cover[blk]
+        assert segs[0][0] == 0 and segs[-1][1] == nkp and all(a[1] == b[0] for a, b in zip(segs, segs[1:]))
+    assert len(set(slots)) == len(slots) and len(cuts) <= plan.sk_max_cut()
+    assert all(2 <= len(v) <= 8 for v in cuts.values())       # a cut block has 2..8 pieces, one per range it spans
+    # balance: no range has more than its share (a multiple of the ring depth) of units
+    work = [sum(b[4 * k + 2] - b[4 * k + 1] for k in range(plan.sk_walk(x, nb, nkp, per, b, 64))) for x in range(8) for b in [buf]]
+    assert max(work) <= per and sum(work) == nb * nkp
