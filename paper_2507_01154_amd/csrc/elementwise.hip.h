@@ -79,7 +79,9 @@ __device__ __forceinline__ void widen8(const u32x4_t v, float* f) {
 
 // out[e] = sum_i c_i * scratch[i][e] + noise_scale * z[e], 8 consecutive elements per thread
 // (16-byte loads from the 16-bit scratch, two Philox groups, two 16-byte stores).  n8 = S / 8.
-template <int DT>
+// DEEP: four samples' loads in flight per thread (the kernels that have the chip to themselves); otherwise one, which
+// keeps the kernel within the registers left over beside a resident contraction workgroup (the overlapped schedule).
+template <int DT, bool DEEP>
 __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch, const float* __restrict__ factors, int B,
                                                 size_t S, size_t v, float noise_scale, uint64_t seed, uint32_t layer,
                                                 float* __restrict__ out, int accumulate);
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(256) void aggregate16_kernel(const void* __restrict
                                                           uint32_t layer, float* __restrict__ out, int accumulate) {
   const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (v >= n8) return;
-  aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
+  aggregate16_one<DT, true>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
 }
 
 // The same work with a fixed, small number of workgroups striding over the elements: the form that runs on
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(256) void aggregate16_persistent_kernel(const void*
                                                                      uint32_t layer, float* __restrict__ out, int accumulate) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += stride)
-    aggregate16_one<DT>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
+    aggregate16_one<DT, false>(scratch, factors, B, S, v, noise_scale, seed, layer, out, accumulate);
 }
 
 // The whole tail of Algorithm 1 after the block-wise synchronisation in one kernel: inter-block reduce and clip
@@ -118,10 +120,10 @@ __global__ __launch_bounds__(256) void clip_aggregate16_kernel(const void* __res
   clip_factors_to_lds(partials, tiles, C, B, fac, out_norms);
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += stride)
-    aggregate16_one<DT>(scratch, fac, B, S, v, noise_scale, seed, layer, out, accumulate);
+    aggregate16_one<DT, true>(scratch, fac, B, S, v, noise_scale, seed, layer, out, accumulate);
 }
 
-template <int DT>
+template <int DT, bool DEEP>
 __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch, const float* __restrict__ factors, int B,
                                                 size_t S, size_t v, float noise_scale, uint64_t seed, uint32_t layer,
                                                 float* __restrict__ out, int accumulate) {
@@ -135,16 +137,56 @@ __device__ __forceinline__ void aggregate16_one(const void* __restrict__ scratch
   }
   const u32x4_t* src = (const u32x4_t*)scratch + v;
   const size_t stride = S / 8;
-  for (int i = 0; i < B; ++i) {
-    const u32x4_t raw = __builtin_nontemporal_load(src + (size_t)i * stride);
-    const float c = factors[i];
-    float f[8];
-    widen8<DT>(raw, f);
+  Normals4 z0 = {}, z1 = {};
+  if constexpr (DEEP) {
+    // Four samples' loads are issued before the first is used (64 bytes in flight per thread), and the noise, which
+    // depends on nothing that is loaded, is generated while they are on their way; the sums keep the sample order.
+    u32x4_t raw[4] = {};
+    const int first = B < 4 ? B : 4;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) acc[q] = fmaf(c, f[q], acc[q]);
+    for (int q = 0; q < 4; ++q)
+      if (q < first) raw[q] = __builtin_nontemporal_load(src + (size_t)q * stride);
+    if (noise_scale != 0.0f) {
+      z0 = noise_group(seed, layer, 2 * v);
+      z1 = noise_group(seed, layer, 2 * v + 1);
+    }
+    int i = 0;
+    while (i < B) {
+      const int n = B - i < 4 ? B - i : 4;
+      u32x4_t cur[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) cur[q] = raw[q];
+      const int nn = B - i - n < 4 ? B - i - n : 4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (q < nn) raw[q] = __builtin_nontemporal_load(src + (size_t)(i + n + q) * stride);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (q < n) {
+          const float c = factors[i + q];
+          float f[8];
+          widen8<DT>(cur[q], f);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[e] = fmaf(c, f[e], acc[e]);
+        }
+      }
+      i += n;
+    }
+  } else {
+    for (int i = 0; i < B; ++i) {
+      const u32x4_t raw = __builtin_nontemporal_load(src + (size_t)i * stride);
+      const float c = factors[i];
+      float f[8];
+      widen8<DT>(raw, f);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[q] = fmaf(c, f[q], acc[q]);
+    }
+    if (noise_scale != 0.0f) {
+      z0 = noise_group(seed, layer, 2 * v);
+      z1 = noise_group(seed, layer, 2 * v + 1);
+    }
   }
   if (noise_scale != 0.0f) {
-    const Normals4 z0 = noise_group(seed, layer, 2 * v), z1 = noise_group(seed, layer, 2 * v + 1);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       acc[q] = fmaf(noise_scale, z0.z[q], acc[q]);

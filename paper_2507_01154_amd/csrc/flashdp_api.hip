@@ -16,6 +16,7 @@
 #include "elementwise.hip.h"
 #include "gemm_mfma.hip.h"
 #include "gemm_mfma_dma.hip.h"
+#include "gemm_mfma_dma_shaped.hip.h"
 #include "gemm_mfma_f32.hip.h"
 #include "gemm_mfma_streamk.hip.h"
 #include "fused_dp.hip.h"
@@ -90,8 +91,11 @@ using Cfg128x4 = TileCfg<128, 128, 64, 2, 2>;   // 4 waves, 64x64 per wave
 using Cfg256x8k32 = TileCfg<256, 256, 32, 2, 4>; // 8 waves, 32-deep k-tiles (half the LDS)
 
 using CfgDma = DmaCfg<4>;                        // 8 waves, 32-deep k-tiles loaded straight into 4 LDS stages
+using CfgDma384x192 = ShapedCfg<384, 192, 4, 2, 4>;   // the same pipeline, 8 waves of 96x96
+using CfgDma192x384 = ShapedCfg<192, 384, 2, 4, 4>;
 
-enum Path { PATH_SIMPLE = 0, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5, PATH_DMA = 6 };
+enum Path { PATH_SIMPLE = 0, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5, PATH_DMA = 6,
+            PATH_DMA_384x192 = 7, PATH_DMA_192x384 = 8 };
 
 struct Plan {
   Path path;         // per-sample passes (norm, spill)
@@ -139,6 +143,22 @@ EnvOverrides env() {
   return live ? read_env() : cached;
 }
 
+// Number of compute units of the current device (looked up once per device).
+int device_cus() {
+  static std::mutex m;
+  static std::map<int, int> cus;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  std::lock_guard<std::mutex> lock(m);
+  auto it = cus.find(dev);
+  if (it == cus.end()) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    it = cus.emplace(dev, n).first;
+  }
+  return it->second;
+}
+
 Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
   Plan p;
   const bool mfma_ok = dtype != FLASHDP_F32 && P % 8 == 0 && D % 8 == 0 &&
@@ -152,7 +172,8 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
     int choice = env().tile;
-    if (choice != PATH_DMA && (choice < PATH_256x8 || choice > PATH_256x8k32)) choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
+    if (choice != PATH_DMA && choice != PATH_DMA_384x192 && choice != PATH_DMA_192x384 && (choice < PATH_256x8 || choice > PATH_256x8k32))
+      choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
     if (choice == 0) {
       // The 256x256 direct-to-LDS kernel unless the problem has too few such work items to occupy the chip:
       // measured on MI355X (scratch schedule, T = 1024..2048, features 768..13824, B = 1..8) it beats the
@@ -164,16 +185,32 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
       // spilled registers, and is no longer built.  The register-staged kernels stay selectable (FLASHDP_TILE).
       const int64_t items = ((D + 255) / 256) * ((P + 255) / 256) * B;
       choice = items >= 128 ? PATH_DMA : PATH_128x4;
+      if (choice == PATH_DMA) {
+        // Work items are equally long, so a per-sample pass takes ceil(items / CUs) rounds of one item each: where
+        // 384x192 or 192x384 tiles (9/8 the work of a 256x256 one) need enough fewer rounds, they are taken
+        // (3072 x 768 at B = 8: 288 items = 2 rounds, against 256 = 1 round of 1.125).  A clear margin is asked for:
+        // the 256x256 kernel is the one tuned and measured on the large layers.
+        const int64_t cus = device_cus() > 0 ? device_cus() : 256;   // sizing calls may come before a device is there
+        auto rounds = [&](int64_t bm, int64_t bn) { return (((D + bm - 1) / bm) * ((P + bn - 1) / bn) * B + cus - 1) / cus; };
+        const double c256 = (double)rounds(256, 256), ca = 1.125 * rounds(384, 192), cb = 1.125 * rounds(192, 384);
+        if (std::min(ca, cb) <= 0.9 * c256) choice = ca <= cb ? PATH_DMA_384x192 : PATH_DMA_192x384;
+      }
     }
     p.path = (Path)choice;
     p.accum_path = p.path;
-    // ... so it needs about the same number of 256x256 tiles by itself before the large tile pays
+    const bool shaped = p.path == PATH_DMA_384x192 || p.path == PATH_DMA_192x384;
+    // the batch-accumulating pass has one workgroup per tile: it needs about the same number of 256x256 tiles by
+    // itself before the large tile pays (and the shaped kernels have no such pass)
+    if (shaped) p.accum_path = ((D + 255) / 256) * ((P + 255) / 256) < 128 ? PATH_128x4 : PATH_DMA;
     if (env().tile == 0 && p.path == PATH_DMA && ((D + 255) / 256) * ((P + 255) / 256) < 128) p.accum_path = PATH_128x4;
     p.bm = p.bn = (p.path == PATH_128x4) ? 128 : 256;
+    if (p.path == PATH_DMA_384x192) { p.bm = 384; p.bn = 192; }
+    if (p.path == PATH_DMA_192x384) { p.bm = 192; p.bn = 384; }
   }
   p.tiles_m = (int)((D + p.bm - 1) / p.bm);
   p.tiles_n = (int)((P + p.bn - 1) / p.bn);
-  const int abm = (p.accum_path == p.path) ? p.bm : 128, abn = (p.accum_path == p.path) ? p.bn : 128;
+  const int abm = (p.accum_path == p.path) ? p.bm : p.accum_path == PATH_128x4 ? 128 : 256;
+  const int abn = (p.accum_path == p.path) ? p.bn : p.accum_path == PATH_128x4 ? 128 : 256;
   p.accum_tiles_m = (int)((D + abm - 1) / abm);
   p.accum_tiles_n = (int)((P + abn - 1) / abn);
   return p;
@@ -182,6 +219,7 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
 const char* path_kernel_name(Path p) {
   switch (p) {
     case PATH_DMA: return "gemm_mfma_dma_kernel";
+    case PATH_DMA_384x192: case PATH_DMA_192x384: return "gemm_mfma_dma_shaped_kernel";
     case PATH_F32: return "gemm_mfma_f32_kernel";
     case PATH_SIMPLE: return "gemm_simple_kernel";
     default: return "gemm_mfma_kernel";
@@ -270,6 +308,14 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& args, hipStream_t st) {
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
       case PATH_256x8k32: return launch_mfma<Cfg256x8k32, MODE, DT>(a, st);
       case PATH_DMA: return launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE, DT>, MODE, a, st, /*lockstep=*/true);
+      case PATH_DMA_384x192:
+        if constexpr (MODE != MODE_ACCUM)
+          return launch_tiled<CfgDma384x192>(gemm_mfma_dma_shaped_kernel<CfgDma384x192, MODE, DT>, MODE, a, st, /*lockstep=*/true);
+        return hipErrorInvalidValue;
+      case PATH_DMA_192x384:
+        if constexpr (MODE != MODE_ACCUM)
+          return launch_tiled<CfgDma192x384>(gemm_mfma_dma_shaped_kernel<CfgDma192x384, MODE, DT>, MODE, a, st, /*lockstep=*/true);
+        return hipErrorInvalidValue;
       default: break;
     }
   }
@@ -383,22 +429,6 @@ int owned_workspace(size_t need, void** ptr, size_t* bytes) {
 int resolve_schedule(int schedule) {
   const int forced = env().schedule;
   return forced >= 0 ? forced : schedule;
-}
-
-// Number of compute units of the current device (looked up once per device).
-int device_cus() {
-  static std::mutex m;
-  static std::map<int, int> cus;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 0;
-  std::lock_guard<std::mutex> lock(m);
-  auto it = cus.find(dev);
-  if (it == cus.end()) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
-    it = cus.emplace(dev, n).first;
-  }
-  return it->second;
 }
 
 // The single-launch form needs a workgroup per 256 x 256 tile resident at the same time (one per CU: its ring takes
@@ -597,7 +627,7 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     bool ok = dtype != FLASHDP_F32 && g_ctx.stages == FLASHDP_STAGE_ALL;
     for (int l = 0; l < n_layers && ok; ++l) {
       const Plan p = make_plan(b, T, layers[l].d_in, layers[l].d_out, dtype);
-      ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
+      ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA || p.path == PATH_DMA_384x192 || p.path == PATH_DMA_192x384) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
     }
     return ok;
   };

@@ -32,3 +32,18 @@ int sk_walk(int xcd, int n_blocks, int nk_pad, int units, int* out, int cap) {
 int sk_slots() { return flashdp::STREAMK_SLOTS; }
 int sk_max_cut() { return flashdp::STREAMK_MAX_CUT; }
 }
+
+// Index arithmetic of the direct-to-LDS kernel for 384 x 192 and 192 x 384 tiles.
+#include "../paper_2507_01154_amd/csrc/shaped_plan.h"
+extern "C" {
+int sp_slots(int bm, int bn) { return flashdp::shaped_plan::slots(bm, bn); }
+int sp_stage_elems(int bm, int bn) { return flashdp::shaped_plan::stage_elems(bm, bn); }
+unsigned sp_lds_bytes_for_loads(int bm, int bn, int stages) { return flashdp::shaped_plan::lds_bytes_for_loads(bm, bn, stages); }
+int sp_slot_operand(int bm, int bn, int slot) { return flashdp::shaped_plan::slot_operand(bm, bn, slot); }
+int sp_slot_index(int bm, int bn, int wave, int slot) { return flashdp::shaped_plan::slot_index(bm, bn, wave, slot); }
+unsigned sp_slot_dst_bytes(int bm, int bn, int stages, int stage, int wave, int slot) { return flashdp::shaped_plan::slot_dst_bytes(bm, bn, stages, stage, wave, slot); }
+int sp_lane_row(int w, int n, int lane) { return flashdp::shaped_plan::lane_row(w, n, lane); }
+int sp_lane_chunk(int w, int n, int lane) { return flashdp::shaped_plan::lane_chunk(w, n, lane); }
+int sp_kept_at(int row, int col, int w) { return flashdp::shaped_plan::kept_at(row, col, w); }
+int sp_frag_offset(int lane, int block, int w) { return flashdp::shaped_plan::frag_offset(lane, block, w); }
+}

@@ -473,10 +473,11 @@ def _random_shapes(n, seed):
 
 
 @pytest.mark.parametrize("shape", _random_shapes(12, 2024))
-@pytest.mark.parametrize("tile", [4, 6])
+@pytest.mark.parametrize("tile", [4, 6, 7, 8])
 def test_random_shapes_both_kernel_families(shape, tile):
     # seeded random (B, T, d_in, d_out) with ragged tiles in every dimension, through the register-staged and the
-    # direct-to-LDS kernel; scratch schedule (norm + spill + aggregation) and the plain batch gradient
+    # direct-to-LDS kernels (6: 256 x 256 tiles, 7: 384 x 192, 8: 192 x 384); scratch schedule (norm + spill +
+    # aggregation) and the plain batch gradient
     B, T, P, D = shape
     base = W.WORKLOADS["gpt2_small_mlp_up"]
     w = W.scaled_down(base, B=B, T=T, dims=[(P, D)])
@@ -488,6 +489,23 @@ def test_random_shapes_both_kernel_families(shape, tile):
     torch.cuda.synchronize()
     want, _ = O.linear_dp_grad(X, dY, 1e30, 0.0, 0, 0)      # nothing clips: the plain batch gradient
     assert rel_fro(out.cpu().numpy(), want) <= 5e-5
+
+
+@pytest.mark.parametrize("shape,kernel", [((8, 70, 768, 3072), "gemm_mfma_dma_shaped_kernel"),      # 288 items of 256 x 256, 256 of 384 x 192
+                                          ((8, 70, 3072, 768), "gemm_mfma_dma_shaped_kernel"),      # the same, 192 x 384
+                                          ((8, 70, 760, 3064), "gemm_mfma_dma_shaped_kernel"),      # ragged edges in both
+                                          ((8, 70, 1024, 3072), "gemm_mfma_dma_kernel")])            # 384 items either way
+@pytest.mark.parametrize("schedule", ["scratch", "twopass", "explicit"])
+def test_tile_shape_follows_the_number_of_rounds(shape, kernel, schedule):
+    # work items of a per-sample pass are equally long: where 384 x 192 (or 192 x 384) tiles need fewer rounds of the
+    # 256 compute units than 256 x 256 tiles, the library takes them
+    B, T, P, D = shape
+    base = W.WORKLOADS["gpt2_small_mlp_up"]
+    w = W.scaled_down(base, B=B, T=T, dims=[(P, D)])
+    X, dY = W.make_layer(w, 0)
+    check_case(X, dY, 1.0, 0.5, 29, 3, "bf16", schedule)
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        assert F.flashdp_last_kernel() == kernel
 
 
 @pytest.mark.parametrize("shape", [(64, 40, 512, 512), (3, 2100, 1024, 776), (9, 130, 1032, 1288), (2, 4000, 776, 1024)])

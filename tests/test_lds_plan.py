@@ -154,3 +154,105 @@ def test_balanced_gradient_walk_covers_every_block_once(plan, shape):
     # balance: no range has more than its share (a multiple of the ring depth) of units
     work = [sum(b[4 * k + 2] - b[4 * k + 1] for k in range(plan.sk_walk(x, nb, nkp, per, b, 64))) for x in range(8) for b in [buf]]
     assert max(work) <= per and sum(work) == nb * nkp
+
+
+# ---- the same pipeline for 384 x 192 and 192 x 384 tiles (csrc/shaped_plan.h) ----
+
+SHAPES = [(384, 192), (192, 384), (256, 256)]
+
+
+def shaped_fill(plan, bm, bn, stage):
+    """What one k-tile's direct loads leave in LDS: element slot -> (operand, tile row, tile column); loads that fetch
+    nothing are recorded apart."""
+    n = plan.sp_stage_elems(bm, bn)
+    total = plan.sp_lds_bytes_for_loads(bm, bn, STAGES) // 2
+    owner = -np.ones((total, 3), dtype=np.int64)
+    writes = np.zeros(total, dtype=np.int64)
+    idle = []
+    for wave in range(WAVES):
+        for slot in range(plan.sp_slots(bm, bn)):
+            op = plan.sp_slot_operand(bm, bn, slot)
+            k = plan.sp_slot_index(bm, bn, wave, slot)
+            base = plan.sp_slot_dst_bytes(bm, bn, STAGES, stage, wave, slot)
+            assert base % 1024 == 0 and base + 1024 <= 2 * total
+            if k < 0:
+                idle.append((wave, slot, base))
+                continue
+            w = bm if op == 0 else bn
+            for lane in range(64):
+                row, chunk = plan.sp_lane_row(w, k, lane), plan.sp_lane_chunk(w, k, lane)
+                assert 0 <= row < 32 and 0 <= chunk < w // 8
+                e0 = (base + 16 * lane) // 2
+                for e in range(8):
+                    owner[e0 + e] = (op, row, 8 * chunk + e)
+                    writes[e0 + e] += 1
+    return owner, writes, idle, n
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("stage", range(STAGES))
+def test_shaped_loads_fill_each_stage_exactly_once(plan, shape, stage):
+    bm, bn = shape
+    owner, writes, idle, n = shaped_fill(plan, bm, bn, stage)
+    lo, hi = stage * n, (stage + 1) * n
+    assert np.all(writes[lo:hi] == 1) and writes.sum() == n
+    for op, w in ((0, bm), (1, bn)):
+        for row in range(32):
+            for col in range(w):
+                slot = lo + op * 32 * bm + plan.sp_kept_at(row, col, w)
+                assert tuple(owner[slot]) == (op, row, col)
+    # instructions without a load write (zeros) behind the ring, each wave to a 1 KB of its own, whatever the stage
+    ring = STAGES * n * 2
+    assert len(idle) == WAVES * plan.sp_slots(bm, bn) - (bm + bn) // 16
+    assert all(base == ring + 1024 * wave for wave, _, base in idle)
+    assert len({wave for wave, _, _ in idle}) == len(idle)          # at most one per wave: no two share a destination
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_shaped_fragment_reads_deliver_the_matrix_core_operand_layout(plan, shape):
+    bm, bn = shape
+    owner, _, _, n = shaped_fill(plan, bm, bn, 2)
+    base = 2 * n
+    for op, w in ((0, bm), (1, bn)):
+        tile0 = base + op * 32 * bm
+        for block in range(w // 32):
+            for ks in range(2):
+                addr = np.zeros((2, 64), dtype=np.int64)
+                for half in range(2):
+                    for lane in range(64):
+                        a = plan.sp_frag_offset(lane, block, w) + ks * 16 * w + half * 4 * w
+                        assert 0 <= a and a + 4 <= 32 * w and (2 * a) % 8 == 0
+                        addr[half, lane] = tile0 + a
+                for lane in range(64):
+                    g, i = lane // 16, lane % 16
+                    for half in range(2):
+                        for j in range(4):
+                            src_lane = 16 * g + (i // 4) + 4 * j
+                            o, row, col = owner[addr[half, src_lane] + (i % 4)]
+                            assert o == op
+                            assert row == 16 * ks + 8 * (lane // 32) + 4 * half + j
+                            assert col == 32 * block + lane % 32
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_shaped_transposed_reads_are_bank_conflict_free(plan, shape):
+    bm, bn = shape
+    for w, tile0 in ((bm, 0), (bn, 32 * bm)):
+        for block in range(w // 32):
+            for ks in range(2):
+                for half in range(2):
+                    for half_wave in range(2):
+                        banks = []
+                        for lane in range(32 * half_wave, 32 * half_wave + 32):
+                            byte = 2 * (tile0 + plan.sp_frag_offset(lane, block, w) + ks * 16 * w + half * 4 * w)
+                            banks += [(byte // 4) % 64, (byte // 4 + 1) % 64]
+                        assert len(set(banks)) == 64
+
+
+def test_shaped_plan_of_the_square_tile_is_the_square_plan(plan):
+    for row in range(32):
+        for col in range(256):
+            assert plan.sp_kept_at(row, col, 256) == plan.plan_kept_at(row, col)
+    for lane in range(64):
+        for block in range(8):
+            assert plan.sp_frag_offset(lane, block, 256) == plan.plan_frag_offset(lane, block)
