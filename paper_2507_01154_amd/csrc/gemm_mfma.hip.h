@@ -150,28 +150,30 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
-// Per-sample passes: work is handed out in blocks of 32 consecutive tiles of one sample (in the band order
-// of tile_coords below that is 8 tile rows x 4 tile columns: 12 operand panels for 32 tiles), block q to XCD
-// q % 8.  Workgroup ids congruent mod 8 share an XCD, so the 32 workgroups resident on an XCD are one such
-// block and share its panels in that XCD's L2, and the eight XCDs work on eight consecutive blocks - almost
-// always of the same sample - at the same time: one sample's operands (tens of MB) stay in the memory-side
-// cache shared by the XCDs for as long as they are needed.  (One sample per XCD made eight working sets compete
-// for that cache; an eighth of every sample per XCD cut the blocks of 32 into pieces.)
-// The grid is 8 * ceil(B * blocks / 8) * 32 workgroups; those beyond the last tile of a block, or beyond the
-// last block, return false and exit at once.
+// Per-sample passes: the work items (sample, tile), sample-major, are handed out in blocks of 32 consecutive items
+// (in the band order of tile_coords below 32 consecutive tiles are 8 tile rows x 4 tile columns: 12 operand panels
+// for 32 tiles), block q to XCD q % 8.  Workgroup ids congruent mod 8 share an XCD, so the 32 workgroups resident on
+// an XCD are one such block and share its panels in that XCD's L2, and the eight XCDs work on eight consecutive
+// blocks - almost always of the same sample - at the same time: one sample's operands (tens of MB) stay in the
+// memory-side cache shared by the XCDs for as long as they are needed.  (One sample per XCD made eight working sets
+// compete for that cache; an eighth of every sample per XCD cut the blocks of 32 into pieces.)
+// Blocks run across sample boundaries, so only the very last block can be short.  (Cutting the blocks per sample
+// left a short block at the end of every sample; with an even number of blocks per sample those all went to the
+// same four XCDs, which then idled: 36 tiles per sample - blocks of 32 and 4 - ran at 0.56 of the rate.)
+// The grid is 8 * ceil(blocks / 8) * 32 workgroups; those beyond the last item return false and exit at once.
 constexpr int SHARE_BLOCK = 32;
 __host__ __device__ __forceinline__ int64_t shared_block_grid(int tiles, int B) {
-  const int64_t blocks = (tiles + SHARE_BLOCK - 1) / SHARE_BLOCK;
-  return 8 * ((B * blocks + 7) / 8) * SHARE_BLOCK;
+  const int64_t blocks = ((int64_t)B * tiles + SHARE_BLOCK - 1) / SHARE_BLOCK;
+  return 8 * ((blocks + 7) / 8) * SHARE_BLOCK;
 }
 __device__ __forceinline__ bool shared_block_item(int bid, int tiles, int B, int* sample, int* tile) {
-  const int blocks = (tiles + SHARE_BLOCK - 1) / SHARE_BLOCK;
   const int xcd = bid & 7, idx = bid >> 3;
   const int q = 8 * (idx / SHARE_BLOCK) + xcd, w = idx % SHARE_BLOCK;
-  const int s = q / blocks, t = (q - s * blocks) * SHARE_BLOCK + w;
+  const int g = q * SHARE_BLOCK + w;   // < grid < 2^31 (checked at launch)
+  const int s = g / tiles;
   *sample = s;
-  *tile = t;
-  return s < B && t < tiles;
+  *tile = g - s * tiles;
+  return g < B * tiles;
 }
 
 // Tiles are walked in bands of GROUP_M tile rows, column by column inside a band, so that consecutive
