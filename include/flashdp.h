@@ -52,11 +52,12 @@
  * Environment overrides (measurement aids, not needed in normal use), read once per process at the first call;
  * with FLASHDP_DEBUG_ENV=1 set at that moment they are read again at every call:
  *   FLASHDP_SCHEDULE = twopass | scratch | overlap | explicit | ghost | fused   replaces the schedule argument;
- *   FLASHDP_TILE = 2 | 3 | 4 | 6 forces the matrix-core kernel (256x256 with 64-deep k-tiles, 128x128,
+ *   FLASHDP_TILE = 2 | 3 | 4 | 6 | 7 | 8 forces the matrix-core kernel (256x256 with 64-deep k-tiles, 128x128,
  *                                256x256 with 32-deep k-tiles - these three stage tiles through registers -,
- *                                256x256 with 32-deep k-tiles loaded straight into LDS);
+ *                                256x256, 384x192, 192x384 with 32-deep k-tiles loaded straight into LDS);
  *                                -1 sends fp32 inputs to the generic kernel;
- *   FLASHDP_OVERLAP_GRID = n     workgroups of the aggregation kernel in the overlapped schedule (512).
+ *   FLASHDP_OVERLAP_GRID = n     workgroups of the aggregation kernel in the overlapped schedule (default: one per
+ *                                compute unit).
  */
 #ifndef FLASHDP_H
 #define FLASHDP_H

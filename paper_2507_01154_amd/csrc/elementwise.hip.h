@@ -110,8 +110,9 @@ __global__ __launch_bounds__(256) void aggregate16_persistent_kernel(const void*
 }
 
 // The whole tail of Algorithm 1 after the block-wise synchronisation in one kernel: inter-block reduce and clip
-// factors (every workgroup for itself, into LDS), then the clipped batch sum with noise as above.
-template <int DT>
+// factors (every workgroup for itself, into LDS), then the clipped batch sum with noise as above.  DEEP as in
+// aggregate16_one: on for the ordinary grid, off for the bounded grid that runs beside a contraction kernel.
+template <int DT, bool DEEP>
 __global__ __launch_bounds__(256) void clip_aggregate16_kernel(const void* __restrict__ scratch, const float* __restrict__ partials,
                                                                int tiles, float C, float* __restrict__ out_norms, int B, size_t S,
                                                                size_t n8, float noise_scale, uint64_t seed, uint32_t layer,
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(256) void clip_aggregate16_kernel(const void* __res
   clip_factors_to_lds(partials, tiles, C, B, fac, out_norms);
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += stride)
-    aggregate16_one<DT, true>(scratch, fac, B, S, v, noise_scale, seed, layer, out, accumulate);
+    aggregate16_one<DT, DEEP>(scratch, fac, B, S, v, noise_scale, seed, layer, out, accumulate);
 }
 
 template <int DT, bool DEEP>

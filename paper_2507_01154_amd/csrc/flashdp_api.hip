@@ -108,7 +108,7 @@ struct Plan {
 // Environment overrides (measurement aids).  Read once per process, at the first call that needs them; with
 // FLASHDP_DEBUG_ENV=1 in the environment at that moment they are read again at every call instead (the test
 // suite switches kernels and schedules between calls this way).
-struct EnvOverrides { int tile = 0; int overlap_grid = 512; int schedule = -1; };
+struct EnvOverrides { int tile = 0; int overlap_grid = 0; int schedule = -1; };
 
 int parse_schedule_name(const char* s) {
   if (!s || !*s) return -1;
@@ -552,7 +552,8 @@ int run_layer(const flashdp_layer_t& L0, int64_t B, int64_t T, int dtype, int mo
                            agg_grid * (size_t)B * tiles * 4 <= (size_t(64) << 20) &&
                            (stages & (FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE)) == (FLASHDP_STAGE_CLIP | FLASHDP_STAGE_AGGREGATE);
     if (fold_clip) {
-      hipLaunchKernelGGL((clip_aggregate16_kernel<DT_BF16>), dim3((unsigned)agg_grid), dim3(256), 0, st, a.scratch, a.partials, tiles,
+      auto kern = persistent_grid > 0 ? clip_aggregate16_kernel<DT_BF16, false> : clip_aggregate16_kernel<DT_BF16, true>;
+      hipLaunchKernelGGL(kern, dim3((unsigned)agg_grid), dim3(256), 0, st, a.scratch, a.partials, tiles,
                          L.C, L.out_norms, (int)B, S, n8_all, noise_scale, L.seed, L.layer, L.out_grad, accumulate ? 1 : 0);
       HIP_TRY(hipGetLastError());
     } else {
@@ -726,7 +727,12 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
       side->ready.push_back(e1);
       side->done.push_back(e2);
     }
-    const int grid = env().overlap_grid;
+    // One aggregation workgroup (4 waves, one load in flight each) per compute unit.  Measured on the Llama-13B
+    // block, ms per step: 9.07-9.16 with 256 workgroups on 256 CUs, 9.22-9.24 with 192-224, 9.29-9.51 with 288-2048
+    // (a CU with two of them falls behind the others that share its operand panels), 9.18-9.19 with 256 workgroups
+    // of 8 waves, 9.23 with four loads in flight per thread (more registers: one wave per SIMD fits beside the
+    // contraction's two, as before, but nothing is gained).
+    const int grid = env().overlap_grid > 0 ? env().overlap_grid : std::max(device_cus(), 1);
     const size_t slot = scratch_need(chunk);
     for (int k = 0; k < n_items; ++k) {
       const Item& it = items[k];
