@@ -628,7 +628,10 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
     bool ok = dtype != FLASHDP_F32 && g_ctx.stages == FLASHDP_STAGE_ALL;
     for (int l = 0; l < n_layers && ok; ++l) {
       const Plan p = make_plan(b, T, layers[l].d_in, layers[l].d_out, dtype);
-      ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA || p.path == PATH_DMA_384x192 || p.path == PATH_DMA_192x384) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
+      // (not the 384x192 / 192x384 kernels: their 248 registers leave no room for an aggregation wave beside two
+      // contraction waves per SIMD, and a bounded aggregation workgroup that takes a CU would keep the next
+      // contraction workgroup out of it until its whole share is done)
+      ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
     }
     return ok;
   };

@@ -378,18 +378,19 @@ def test_gradient_accumulation_over_micro_batches(schedule, shape):
     assert rel_fro(res[0.0], whole.astype(np.float64)) <= 1e-6
 
 
+@pytest.mark.parametrize("tile", [6, 7, 8])
 @pytest.mark.parametrize("schedule", ["twopass", "scratch", "ghost"])
-def test_direct_to_lds_kernel_f16_inputs_and_accumulation(schedule):
-    # the large-shape kernel (forced here on a small ragged shape): fp16 operands, and the accumulate flag of its
-    # batch-summing mode across two micro-batches
+def test_direct_to_lds_kernel_f16_inputs_and_accumulation(schedule, tile):
+    # the large-shape kernels (forced here on a small ragged shape; 6: 256 x 256 tiles, 7: 384 x 192, 8: 192 x 384):
+    # fp16 operands, and the accumulate flag of the batch-summing mode across two micro-batches
     rng = np.random.default_rng(77)
     B, T, P, D = 4, 100, 264, 520
     X16 = rng.standard_normal((B, T, P)).astype(np.float16)
     dY16 = (rng.standard_normal((B, T, D)) * 0.05 * (10.0 ** rng.uniform(-1, 1, size=(B, 1, 1)))).astype(np.float16)
     want = O.linear_dp_grad(X16.astype(np.float32), dY16.astype(np.float32), 1.0, 0.0, 9, 2)
-    check_case(X16, dY16, 1.0, 1.0, 9, 2, "f16", schedule, tile=6, oracle=want)
+    check_case(X16, dY16, 1.0, 1.0, 9, 2, "f16", schedule, tile=tile, oracle=want)
     out = torch.full((D, P), float("nan"), device=DEV)
-    with env(FLASHDP_TILE=6):
+    with env(FLASHDP_TILE=tile):
         for k, (a0, a1) in enumerate([(0, 3), (3, 4)]):
             L = [dict(X=to_device(X16[a0:a1]), dY=to_device(dY16[a0:a1]), d_in=P, d_out=D, C=1.0, sigma=0.0, seed=9, layer=2,
                       out_grad=out, out_norms=None)]
