@@ -92,6 +92,34 @@ def test_workspace_bytes_formula():
     assert L.flashdp_set_schedule(0) == F.OK
 
 
+def test_tile_shape_follows_the_rounds_of_equally_long_work_items(monkeypatch):
+    # host logic only, read off the number of norm partials (B x tiles floats, rounded up to 256 bytes) in the two-pass
+    # workspace.  Without a device 256 compute units are assumed.
+    mk = lambda p, d: [dict(X=None, dY=None, d_in=p, d_out=d, C=1.0, sigma=1.0, seed=0, layer=0, out_grad=None)]
+
+    def partial_bytes(p, d, B, T, tile=None):
+        if tile is None:
+            monkeypatch.delenv("FLASHDP_TILE", raising=False)
+        else:
+            monkeypatch.setenv("FLASHDP_TILE", str(tile))
+        n = F.flashdp_workspace_bytes(mk(p, d), B, T, F.BF16, "twopass")
+        monkeypatch.delenv("FLASHDP_TILE", raising=False)
+        return n - 256          # the clip factors take the first 256 bytes (B <= 64)
+
+    up = lambda n: (n + 255) // 256 * 256
+    # 768 -> 3072 at B = 8: 36 tiles of 256 x 256 (288 items, two rounds) against 32 of 384 x 192 (256 items, one round)
+    assert partial_bytes(768, 3072, 8, 1024, tile=6) == up(8 * 36 * 4)
+    assert partial_bytes(768, 3072, 8, 1024) == up(8 * 32 * 4)
+    assert partial_bytes(3072, 768, 8, 1024) == up(8 * 32 * 4)              # transposed: 192 x 384
+    assert partial_bytes(768, 3072, 8, 1024, tile=7) == up(8 * 32 * 4)
+    # the Llama shapes keep 256 x 256: 400 / 1080 / 256 tiles
+    assert partial_bytes(5120, 5120, 8, 2048) == up(8 * 400 * 4)
+    assert partial_bytes(5120, 13824, 8, 2048) == up(8 * 1080 * 4)
+    assert partial_bytes(4096, 4096, 4, 2048) == up(4 * 256 * 4)
+    # equal tile-rounds (1024 x 3072 at B = 8: 384 items either way): the square tile stays
+    assert partial_bytes(1024, 3072, 8, 1024) == up(8 * 48 * 4)
+
+
 @pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a host without a GPU")
 def test_no_device_is_an_error_not_a_crash():
     assert F.lib().flashdp_linear_dp_grad(A, B_, 1, 1, 8, 8, 1.0, 0.0, 0, O_, None) == F.NO_DEVICE
