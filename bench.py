@@ -71,7 +71,7 @@ def write_traffic(fetch_dir, write_dir, workload, schedule, kernel):
             table = json.load(f)
     except (OSError, ValueError):
         table = {"entries": []}
-    name = "gemm_mfma_dma_kernel" if "gemm_mfma_dma_kernel" in kernel else kernel
+    name = kernel.split("<")[0]
     entry = {"workload": workload, "schedule": schedule, "kernel": name, "profiler_kernel_match": kernel,
              "read_bytes": round(rd), "write_bytes": round(wr), "fetch_size_scale": round(rscale, 4), "write_size_scale": round(wscale, 4),
              "dispatches_averaged": [n_r, n_w], "commit": commit, "date": datetime.date.today().isoformat(),
@@ -105,7 +105,7 @@ def parse():
     ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="no benchmark: read two rocprofv3 --pmc output folders (FETCH_SIZE, WRITE_SIZE runs of this script with "
                          "--copy-probe) and record the dominant kernel's measured bytes per launch in profiles/traffic.json")
-    ap.add_argument("--traffic-kernel", default="gemm_mfma_dma_kernel<flashdp::DmaCfg<4>, 1,",
+    ap.add_argument("--traffic-kernel", default="gemm_mfma_dma16_kernel<flashdp::DmaCfg<4>, 1,",
                     help="substring of the profiler's kernel name to average over (default: the contraction kernel in its parking mode)")
     ap.add_argument("--vendor-envelope", action="store_true",
                     help="also time the vendor GEMM (torch.matmul) on 8192^3 bf16 in its best layout (reduction index contiguous for both "
@@ -175,7 +175,7 @@ def mfma_only(F, torch, dev):
     flop = wgs * 8 * iters * 16 * 32768.0
     out = {}
     for name, pattern in (("zeros", 0), ("random", 1), ("lds_zeros", 2), ("lds_random", 3), ("random_shared_operand_order", 4),
-                          ("random_one_operand_pair", 5), ("random_wide_exponents", 6)):
+                          ("random_one_operand_pair", 5), ("random_wide_exponents", 6), ("random_16x16x32", 7), ("lds_random_16x16x32", 8), ("zeros_16x16x32", 9)):
         ms = time_events(lambda: F.flashdp_mfma_probe(pattern, iters, wgs, sink), 3, 2)
         out[name + "_tflops"] = round(flop / ms / 1e9, 1)
     return out

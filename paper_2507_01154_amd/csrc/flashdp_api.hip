@@ -17,6 +17,7 @@
 #include "gemm_mfma.hip.h"
 #include "gemm_mfma_dma.hip.h"
 #include "gemm_mfma_dma_shaped.hip.h"
+#include "gemm_mfma_dma16.hip.h"
 #include "gemm_mfma_f32.hip.h"
 #include "gemm_mfma_streamk.hip.h"
 #include "fused_dp.hip.h"
@@ -95,7 +96,7 @@ using CfgDma384x192 = ShapedCfg<384, 192, 4, 2, 4>;   // the same pipeline, 8 wa
 using CfgDma192x384 = ShapedCfg<192, 384, 2, 4, 4>;
 
 enum Path { PATH_SIMPLE = 0, PATH_256x8 = 2, PATH_128x4 = 3, PATH_256x8k32 = 4, PATH_F32 = 5, PATH_DMA = 6,
-            PATH_DMA_384x192 = 7, PATH_DMA_192x384 = 8 };
+            PATH_DMA_384x192 = 7, PATH_DMA_192x384 = 8, PATH_DMA16 = 9 };
 
 struct Plan {
   Path path;         // per-sample passes (norm, spill)
@@ -172,7 +173,7 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     p.path = p.accum_path = PATH_SIMPLE; p.bm = 64; p.bn = 64;
   } else {
     int choice = env().tile;
-    if (choice != PATH_DMA && choice != PATH_DMA_384x192 && choice != PATH_DMA_192x384 && (choice < PATH_256x8 || choice > PATH_256x8k32))
+    if (choice != PATH_DMA && choice != PATH_DMA16 && choice != PATH_DMA_384x192 && choice != PATH_DMA_192x384 && (choice < PATH_256x8 || choice > PATH_256x8k32))
       choice = 0;   // (-1 only switches the fp32 matrix-core kernel off)
     if (choice == 0) {
       // The 256x256 direct-to-LDS kernel unless the problem has too few such work items to occupy the chip:
@@ -182,10 +183,12 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
       // Llama-13B block, B = 8, spill pass, N(0,1) data: 8 waves of 128x64 with 32-deep
       // k-tiles loaded straight into LDS 1.22 PFLOP/s; the same tiling with the tiles staged through
       // registers 1.07 (32-deep) resp. 1.0 (64-deep); 4 waves of 128x128 (one wave per SIMD) reached 0.96 and
-      // spilled registers, and is no longer built.  The register-staged kernels stay selectable (FLASHDP_TILE).
+      // spilled registers, and is no longer built.  The same pipeline on the 16x16x32 matrix-core instruction
+      // (gemm_mfma_dma16_kernel, the default) 1.26-1.33 against 1.18-1.28 for the 32x32x16 form on the same boxes:
+      // the part clocks higher on it.  The other kernels stay selectable (FLASHDP_TILE).
       const int64_t items = ((D + 255) / 256) * ((P + 255) / 256) * B;
-      choice = items >= 128 ? PATH_DMA : PATH_128x4;
-      if (choice == PATH_DMA) {
+      choice = items >= 128 ? PATH_DMA16 : PATH_128x4;
+      if (choice == PATH_DMA16) {
         // Work items are equally long, so a per-sample pass takes ceil(items / CUs) rounds of one item each: where
         // 384x192 or 192x384 tiles (9/8 the work of a 256x256 one) need enough fewer rounds, they are taken
         // (3072 x 768 at B = 8: 288 items = 2 rounds, against 256 = 1 round of 1.125).  A clear margin is asked for:
@@ -201,8 +204,8 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
     const bool shaped = p.path == PATH_DMA_384x192 || p.path == PATH_DMA_192x384;
     // the batch-accumulating pass has one workgroup per tile: it needs about the same number of 256x256 tiles by
     // itself before the large tile pays (and the shaped kernels have no such pass)
-    if (shaped) p.accum_path = ((D + 255) / 256) * ((P + 255) / 256) < 128 ? PATH_128x4 : PATH_DMA;
-    if (env().tile == 0 && p.path == PATH_DMA && ((D + 255) / 256) * ((P + 255) / 256) < 128) p.accum_path = PATH_128x4;
+    if (shaped) p.accum_path = ((D + 255) / 256) * ((P + 255) / 256) < 128 ? PATH_128x4 : PATH_DMA16;
+    if (env().tile == 0 && p.path == PATH_DMA16 && ((D + 255) / 256) * ((P + 255) / 256) < 128) p.accum_path = PATH_128x4;
     p.bm = p.bn = (p.path == PATH_128x4) ? 128 : 256;
     if (p.path == PATH_DMA_384x192) { p.bm = 384; p.bn = 192; }
     if (p.path == PATH_DMA_192x384) { p.bm = 192; p.bn = 384; }
@@ -219,6 +222,7 @@ Plan make_plan(int64_t B, int64_t T, int64_t P, int64_t D, int dtype) {
 const char* path_kernel_name(Path p) {
   switch (p) {
     case PATH_DMA: return "gemm_mfma_dma_kernel";
+    case PATH_DMA16: return "gemm_mfma_dma16_kernel";
     case PATH_DMA_384x192: case PATH_DMA_192x384: return "gemm_mfma_dma_shaped_kernel";
     case PATH_F32: return "gemm_mfma_f32_kernel";
     case PATH_SIMPLE: return "gemm_simple_kernel";
@@ -308,6 +312,7 @@ hipError_t launch_gemm_dt(const Plan& p, const GemmArgs& args, hipStream_t st) {
       case PATH_128x4: return launch_mfma<Cfg128x4, MODE, DT>(a, st);
       case PATH_256x8k32: return launch_mfma<Cfg256x8k32, MODE, DT>(a, st);
       case PATH_DMA: return launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE, DT>, MODE, a, st, /*lockstep=*/true);
+      case PATH_DMA16: return launch_tiled<CfgDma>(gemm_mfma_dma16_kernel<CfgDma, MODE, DT>, MODE, a, st, /*lockstep=*/true);
       case PATH_DMA_384x192:
         if constexpr (MODE != MODE_ACCUM)
           return launch_tiled<CfgDma384x192>(gemm_mfma_dma_shaped_kernel<CfgDma384x192, MODE, DT>, MODE, a, st, /*lockstep=*/true);
@@ -631,7 +636,7 @@ int flashdp_block_dp_grad_micro(const flashdp_layer_t* layers, int n_layers, int
       // (not the 384x192 / 192x384 kernels: their 248 registers leave no room for an aggregation wave beside two
       // contraction waves per SIMD, and a bounded aggregation workgroup that takes a CU would keep the next
       // contraction workgroup out of it until its whole share is done)
-      ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
+      ok = (p.path == PATH_256x8k32 || p.path == PATH_256x8 || p.path == PATH_DMA || p.path == PATH_DMA16) && ((size_t)layers[l].d_in * layers[l].d_out) % 8 == 0;
     }
     return ok;
   };
@@ -929,13 +934,13 @@ int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* 
 }
 
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream) {
-  if (pattern < 0 || pattern > 6 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
+  if (pattern < 0 || pattern > 9 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
     return FLASHDP_INVALID_ARGUMENT;
   int dev = 0;
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
-  if (pattern == 2 || pattern == 3) {   // zeros / random with the operand fragments re-read from LDS every k-step
-    hipLaunchKernelGGL(mfma_lds_probe_kernel, dim3((unsigned)workgroups), dim3(512), lds_plan::STAGE_ELEMS * 2, static_cast<hipStream_t>(stream), pattern - 2, iters, sink);
+  if (pattern == 2 || pattern == 3 || pattern == 8) {   // zeros / random with the operand fragments re-read from LDS every k-step (8: random, 16x16x32)
+    hipLaunchKernelGGL(mfma_lds_probe_kernel, dim3((unsigned)workgroups), dim3(512), lds_plan::STAGE_ELEMS * 2, static_cast<hipStream_t>(stream), pattern == 8 ? 5 : pattern - 2, iters, sink);
   } else {
     hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), pattern, iters, sink);
   }
@@ -955,7 +960,7 @@ int64_t flashdp_contraction_timeline(const void* X, const void* dY, int64_t B, i
   st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
   Plan plan = make_plan(B, T, d_in, d_out, FLASHDP_BF16);
-  plan.path = plan.accum_path = PATH_DMA; plan.bm = plan.bn = 256;
+  plan.path = plan.accum_path = PATH_DMA16; plan.bm = plan.bn = 256;
   plan.tiles_m = (int)((d_out + 255) / 256); plan.tiles_n = (int)((d_in + 255) / 256);
   const WsLayout wl = ws_layout(plan, B, T, d_in, d_out, FLASHDP_BF16, park ? FLASHDP_SCHEDULE_SCRATCH : FLASHDP_SCHEDULE_TWOPASS);
   if (workspace_bytes < wl.total) return FLASHDP_WORKSPACE_TOO_SMALL;
@@ -969,8 +974,14 @@ int64_t flashdp_contraction_timeline(const void* X, const void* dY, int64_t B, i
   a.trace = reinterpret_cast<unsigned long long*>(trace);
   const int64_t grid = shared_block_grid(plan.tiles_m * plan.tiles_n, (int)B);
   if (trace_entries < grid) return FLASHDP_WORKSPACE_TOO_SMALL;
-  if (park) HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE_SPILL, DT_BF16, true>, MODE_SPILL, a, static_cast<hipStream_t>(stream), true));
-  else HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE_NORM, DT_BF16, true>, MODE_NORM, a, static_cast<hipStream_t>(stream), true));
+  const bool small_blocks = env().tile != PATH_DMA;   // the kernel the library takes by default
+  if (small_blocks) {
+    if (park) HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma16_kernel<CfgDma, MODE_SPILL, DT_BF16, true>, MODE_SPILL, a, static_cast<hipStream_t>(stream), true));
+    else HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma16_kernel<CfgDma, MODE_NORM, DT_BF16, true>, MODE_NORM, a, static_cast<hipStream_t>(stream), true));
+  } else {
+    if (park) HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE_SPILL, DT_BF16, true>, MODE_SPILL, a, static_cast<hipStream_t>(stream), true));
+    else HIP_TRY(launch_tiled<CfgDma>(gemm_mfma_dma_kernel<CfgDma, MODE_NORM, DT_BF16, true>, MODE_NORM, a, static_cast<hipStream_t>(stream), true));
+  }
   return grid;
 }
 

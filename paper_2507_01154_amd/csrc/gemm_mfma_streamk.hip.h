@@ -2,8 +2,8 @@
 // over the chip whatever the tile count: the comparator the DP path is held against, so that its ratio is not
 // flattered by a plain GEMM whose last round of workgroups runs half empty (400 tiles of 256x256 on 256 CUs).
 //
-// Same tile, ring of direct-to-LDS loads, fragment reads and matrix-core loop as gemm_mfma_dma_kernel in its
-// batch-accumulating mode; what differs is who computes what.  The output is cut into blocks of 32 tiles (8 tile
+// Same tile, ring of direct-to-LDS loads, fragment reads and matrix-core loop as gemm_mfma_dma16_kernel in its
+// batch-accumulating mode (the loop itself is shared: contract16); what differs is who computes what.  The output is cut into blocks of 32 tiles (8 tile
 // rows x 4 tile columns, the group that shares 12 operand panels in one XCD's L2).  A block costs nk k-tiles of
 // time on the 32 CUs of one XCD (nk = all samples' k-tiles, one after the other).  The 8 XCDs are each dealt the
 // same number of (block, k-tile) units, a contiguous range: an XCD walks its range block by block, its 32 workgroups
@@ -15,7 +15,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "gemm_mfma_dma.hip.h"
+#include "gemm_mfma_dma16.hip.h"
 #include "streamk_plan.h"
 
 namespace flashdp {
@@ -42,9 +42,8 @@ struct StreamKCuts {
 };
 
 template <typename Cfg, int DT>
-__global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_streamk_kernel(const StreamKArgs a) {
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, FM = Cfg::FM, FN = Cfg::FN, STAGES = Cfg::STAGES;
-  constexpr int ROW = 256;
+__global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) __attribute__((amdgpu_num_vgpr(DMA16_VGPR_ATTR))) void gemm_mfma_streamk_kernel(const StreamKArgs a) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
   extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -53,19 +52,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_streamk_
   const int xcd = blockIdx.x & 7, w = blockIdx.x >> 3;
   const int tiles = a.tiles_m * a.tiles_n;
 
-  const int d_row = lds_plan::load_row(wave, lane);
-  const int d_chunk = lds_plan::load_chunk(wave, lane);
+  const int d_row = lds_plan16::load_row(wave, lane);
+  const int d_chunk = lds_plan16::load_chunk(wave, lane);
   const uint32_t a_half = (uint32_t)(16 * a.D) * 2u, b_half = (uint32_t)(16 * a.P) * 2u;
   const uint32_t a_kstep = (uint32_t)(BK * a.D) * 2u, b_kstep = (uint32_t)(BK * a.P) * 2u;
   const uint32_t a_bytes = (uint32_t)a.T * (uint32_t)a.D * 2u, b_bytes = (uint32_t)a.T * (uint32_t)a.P * 2u;
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned short*)lds;
   const int kt_per_sample = (a.T + BK - 1) / BK;
-
-  int a_rd[FM], b_rd[FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i) a_rd[i] = lds_plan::frag_offset(lane, wave_m * FM + i);
-#pragma unroll
-  for (int j = 0; j < FN; ++j) b_rd[j] = Cfg::A_ELEMS + lds_plan::frag_offset(lane, wave_n * FN + j);
 
   streamk_walk(xcd, a.n_blocks, a.nk_pad, a.units_per_xcd, [&](const StreamKPiece& pc) {
     const int tile = pc.block * STREAMK_WG_PER_XCD + w;
@@ -87,102 +80,43 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_EU) void gemm_mfma_streamk_
       const char* pb = (const char*)a.X + (size_t)ld_s * b_bytes;
       const u32x4_t rsa = make_rsrc_words(pa, a_bytes), rsb = make_rsrc_words(pb, b_bytes);
       const uint32_t ao = a_off0 + (uint32_t)ld_kt * a_kstep, bo = b_off0 + (uint32_t)ld_kt * b_kstep;
-      load_to_lds(rsa, ao, lds_base + lds_plan::load_dst_bytes(stage, 0, wave, 0));
-      load_to_lds(rsa, ao + a_half, lds_base + lds_plan::load_dst_bytes(stage, 0, wave, 1));
-      load_to_lds(rsb, bo, lds_base + lds_plan::load_dst_bytes(stage, 1, wave, 0));
-      load_to_lds(rsb, bo + b_half, lds_base + lds_plan::load_dst_bytes(stage, 1, wave, 1));
+      load_to_lds(rsa, ao, lds_base + lds_plan16::load_dst_bytes(stage, 0, wave, 0));
+      load_to_lds(rsa, ao + a_half, lds_base + lds_plan16::load_dst_bytes(stage, 0, wave, 1));
+      load_to_lds(rsb, bo, lds_base + lds_plan16::load_dst_bytes(stage, 1, wave, 0));
+      load_to_lds(rsb, bo + b_half, lds_base + lds_plan16::load_dst_bytes(stage, 1, wave, 1));
       ld_kt += 1;
       const bool wrap = ld_kt >= kt_per_sample && ld_s + 1 < a.B;
       ld_s = wrap ? ld_s + 1 : ld_s;
       ld_kt = wrap ? 0 : ld_kt;
     };
 
-    f32x16_t acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    s16x8_t fa[2][FM], fb[2][FN];
-    auto load_frags = [&](int stage, int ks, s16x8_t* pfa, s16x8_t* pfb) {
-      const unsigned short* base = lds + stage * Cfg::STAGE_ELEMS + ks * 16 * ROW;
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const s16x4_t lo = lds_read_tr(base + a_rd[i]);
-        const s16x4_t hi = lds_read_tr(base + a_rd[i] + 4 * ROW);
-        pfa[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      }
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const s16x4_t lo = lds_read_tr(base + b_rd[j]);
-        const s16x4_t hi = lds_read_tr(base + b_rd[j] + 4 * ROW);
-        pfb[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      }
-    };
-
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) issue_loads(s);
-    wait_loads_outstanding<4 * (STAGES - 2)>();   // the first k-tile has landed (and the previous piece's stores are done)
-    __syncthreads();
-    load_frags(0, 0, fa[0], fb[0]);
-
-    constexpr int N_MMA = FM * FN, N_RD = 2 * (FM + FN);
-    auto k_tile = [&](auto cur_c) {
-      constexpr int cur = decltype(cur_c)::value;
-      constexpr int nxt = (cur + 1) % STAGES, refill = (cur + STAGES - 1) % STAGES;
-      load_frags(cur, 1, fa[1], fb[1]);
-      issue_loads(refill);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma32<DT>(fb[0][j], fa[0][i], acc[i][j]);
-      sched_interleave<0, N_MMA, N_RD, 0, 0>();
-      wait_loads_outstanding<4 * (STAGES - 2)>();
-      __syncthreads();
-      load_frags(nxt, 0, fa[0], fb[0]);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma32<DT>(fb[1][j], fa[1][i], acc[i][j]);
-      sched_interleave<0, N_MMA, N_RD, 0, 0>();
-    };
     // k1 - k0 is a multiple of the ring depth (range boundaries and nk_pad are); the k-tiles between the true end
-    // of the reduction and nk_pad read the zeros the parked loads deliver.  The loads issued past k1 land in stages
-    // nobody reads again before the next piece's own loads replace them.
-    for (int k = pc.k0; k < pc.k1; k += STAGES) {
-      static_for<STAGES>([&](auto s_c) { k_tile(s_c); });
-    }
-    wait_loads_outstanding<0>();
-    __syncthreads();   // every wave is done with the ring before the next piece refills it
+    // of the reduction and nk_pad read the zeros the parked loads deliver.  The main loop returns with every load
+    // landed and the workgroup past a barrier: the next piece may refill the ring at once.
+    f32x4_t acc[8][4];
+    contract16<Cfg, DT>(acc, lds_base, lane, wave_m, wave_n, pc.k1 - pc.k0, issue_loads, [](int) {}, []() {});
 
-    // acc[i][j][4q + r] = G[m0 + wave_m*TM + 32i + lane%32][n0 + wave_n*TN + 32j + 8q + 4(lane/32) + r]
-    const int r_in = wave_m * Cfg::TM + (lane & 31), c_in = wave_n * Cfg::TN + 4 * (lane >> 5);
+    // acc[i][j][r] = G[m0 + wave_m*128 + 16 i + lane%16][n0 + wave_n*64 + 16 j + 4 (lane/16) + r]
+    const int r_in = wave_m * 128 + (lane & 15), c_in = wave_n * 64 + 4 * (lane >> 4);
     if (pc.slot < 0) {
 #pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int row = m0 + r_in + i * 32;
+      for (int i = 0; i < 8; ++i) {
+        const int row = m0 + r_in + i * 16;
         if (row >= a.D) continue;
         float* prow = a.out + (size_t)row * a.P;
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int col = n0 + c_in + j * 32 + 8 * q;
-            if (col < a.P) *(float4*)(prow + col) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-          }
+        for (int j = 0; j < 4; ++j) {
+          const int col = n0 + c_in + j * 16;
+          if (col < a.P) *(float4*)(prow + col) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+        }
       }
     } else {
       float* pt = a.partial + ((size_t)pc.slot * STREAMK_WG_PER_XCD + w) * (BM * BN);
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            *(float4*)(pt + (size_t)(r_in + i * 32) * BN + c_in + j * 32 + 8 * q) =
-                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        for (int j = 0; j < 4; ++j)
+          *(float4*)(pt + (size_t)(r_in + i * 16) * BN + c_in + j * 16) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
     }
   });
 }

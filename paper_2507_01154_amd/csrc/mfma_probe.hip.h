@@ -17,7 +17,9 @@ namespace flashdp {
 // 4: the values of 1 with the instructions in boustrophedon order (consecutive instructions of a wave share one
 // operand fragment); 5: the values of 1 with one and the same operand pair for every instruction; 6: pseudo-random
 // values with eight different exponents (2^-7 .. 2) instead of two.  4-6 answer whether the rate on random data
-// depends on how operands are delivered or on the values themselves.
+// depends on how operands are delivered or on the values themselves.  7: the values of 1 through
+// v_mfma_f32_16x16x32_bf16 (two per 32x32x16 instruction of the other patterns: the same FLOPs, half the reuse of
+// an operand element inside the instruction); 9: the same instruction on zeros (its issue-limited rate).
 __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int iters, float* __restrict__ sink) {
   const uint32_t gid = blockIdx.x * 512u + threadIdx.x;
   s16x8_t fa[2][4], fb[2][2];
@@ -29,7 +31,7 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
       // sign and 7 mantissa bits from the hash, exponent of 0.5 .. 2 (pattern 6: of 2^-7 .. 2)
       const uint32_t ex = pattern == 6 ? 120u + ((h >> 16) % 8u) : 126u + ((h >> 16) % 2u);
       const uint32_t bits = (h & 0x8000u) | (ex << 7) | (h & 0x7Fu);
-      f[e] = pattern ? (short)bits : (short)0;
+      f[e] = (pattern && pattern != 9) ? (short)bits : (short)0;
     }
   };
 #pragma unroll
@@ -58,6 +60,35 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
             acc[i][j] = mfma32<DT_BF16>(fb[s][j], fa[s][i], acc[i][j]);
           }
     }
+  } else if (pattern == 7 || pattern == 9) {
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    f32x4_t small[4][2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) small[i][j][h] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+              small[i][j][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fb[s][j]), __builtin_bit_cast(bf16x8_t, fa[s][i]),
+                                                                       small[i][j][h], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][e] += small[i][j][h][e];
   } else if (pattern == 5) {
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
@@ -98,7 +129,7 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
     uint32_t h = ((uint32_t)e * 0x9E3779B9u) ^ (blockIdx.x * 0x85EBCA6Bu);
     h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 12; h *= 0x297A2D39u; h ^= h >> 15;
     const uint32_t bits = (h & 0x8000u) | ((126u + ((h >> 16) % 2u)) << 7) | (h & 0x7Fu);
-    lds[e] = pattern ? (unsigned short)bits : (unsigned short)0;
+    lds[e] = (pattern & 1) ? (unsigned short)bits : (unsigned short)0;
   }
   __syncthreads();
   int a_rd[4], b_rd[2];
@@ -130,6 +161,39 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
   load_frags(0, fa[0], fb[0]);
+  if (pattern & 4) {   // the same fragment traffic feeding 16x16x32 instructions, two per 32x32x16 one
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    f32x4_t small[4][2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) small[i][j][h] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int it = 0; it < iters; ++it) {
+      static_for<2>([&](auto ks_c) {
+        constexpr int ks = decltype(ks_c)::value;
+        load_frags(ks ^ 1, fa[ks ^ 1], fb[ks ^ 1]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+              small[i][j][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fb[ks][j]), __builtin_bit_cast(bf16x8_t, fa[ks][i]),
+                                                                       small[i][j][h], 0, 0, 0);
+        sched_interleave<0, 16, 12, 0, 0>();
+      });
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][e] += small[i][j][h][e];
+  } else {
   for (int it = 0; it < iters; ++it) {
     static_for<2>([&](auto ks_c) {
       constexpr int ks = decltype(ks_c)::value;
@@ -140,6 +204,7 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
         for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT_BF16>(fb[ks][j], fa[ks][i], acc[i][j]);
       sched_interleave<0, 8, 12, 0, 0>();
     });
+  }
   }
   float t = 0.0f;
 #pragma unroll

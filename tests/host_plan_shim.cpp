@@ -47,3 +47,14 @@ int sp_lane_chunk(int w, int n, int lane) { return flashdp::shaped_plan::lane_ch
 int sp_kept_at(int row, int col, int w) { return flashdp::shaped_plan::kept_at(row, col, w); }
 int sp_frag_offset(int lane, int block, int w) { return flashdp::shaped_plan::frag_offset(lane, block, w); }
 }
+
+// Index arithmetic of the direct-to-LDS kernel built on the 16x16x32 matrix-core instruction.
+#include "../paper_2507_01154_amd/csrc/lds_plan16.h"
+extern "C" {
+int p16_load_row(int wave, int lane) { return flashdp::lds_plan16::load_row(wave, lane); }
+int p16_load_chunk(int wave, int lane) { return flashdp::lds_plan16::load_chunk(wave, lane); }
+unsigned p16_load_dst_bytes(int stage, int operand, int wave, int q) { return flashdp::lds_plan16::load_dst_bytes(stage, operand, wave, q); }
+int p16_kept_at(int row, int col) { return flashdp::lds_plan16::kept_at(row, col); }
+int p16_frag_offset(int lane, int block) { return flashdp::lds_plan16::frag_offset(lane, block); }
+int p16_tile_base(int stage, int operand) { return flashdp::lds_plan16::tile_base(stage, operand); }
+}

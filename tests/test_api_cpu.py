@@ -169,14 +169,16 @@ def test_register_budget_of_the_overlapped_schedule():
         if m and cur:
             usage[cur][m.group(1)] = int(m.group(2))
     up8 = lambda n: (n + 7) // 8 * 8
-    spill = [k for k in usage if "gemm_mfma_dma_kernel" in k and "ELi1ELi" in k and k.endswith("Lb0EEEvNS_8GemmArgsE")]   # MODE_SPILL, bf16 and f16, untraced
+    # MODE_SPILL, bf16 and f16, untraced, of the two 256 x 256 direct-to-LDS kernels (16x16x32: the default; 32x32x16)
+    spill = [k for k in usage if ("gemm_mfma_dma_kernel" in k or "gemm_mfma_dma16_kernel" in k) and "ELi1ELi" in k and k.endswith("Lb0EEEvNS_8GemmArgsE")]
     # the streaming kernels that run beside it: the bounded-grid forms (clip factors folded in, one load in flight; and
     # the plain one used when the factors come from a launch of their own)
     agg = [k for k in usage if "aggregate16_persistent_kernel" in k or ("clip_aggregate16_kernel" in k and "Lb0EEE" in k)]
-    assert len(spill) == 2 and len(agg) == 2
+    assert len(spill) == 4 and len(agg) == 2
+    # one aggregation workgroup per CU = one of its waves per SIMD beside two contraction waves
     for k in spill:
         for g in agg:
-            assert 2 * up8(usage[k]["VGPRs"] + usage[k]["AGPRs"]) + 2 * up8(usage[g]["VGPRs"]) <= 512, (k, usage[k], g, usage[g])
+            assert 2 * up8(usage[k]["VGPRs"] + usage[k]["AGPRs"]) + up8(usage[g]["VGPRs"]) <= 512, (k, usage[k], g, usage[g])
     # and no kernel of the library spills registers to memory - except the single-launch comparison kernel, which keeps
     # a dozen values of its sample-boundary code in memory across the main loop (none is touched inside the loop)
     for k, u in usage.items():

@@ -378,7 +378,7 @@ def test_gradient_accumulation_over_micro_batches(schedule, shape):
     assert rel_fro(res[0.0], whole.astype(np.float64)) <= 1e-6
 
 
-@pytest.mark.parametrize("tile", [6, 7, 8])
+@pytest.mark.parametrize("tile", [6, 7, 8, 9])
 @pytest.mark.parametrize("schedule", ["twopass", "scratch", "ghost"])
 def test_direct_to_lds_kernel_f16_inputs_and_accumulation(schedule, tile):
     # the large-shape kernels (forced here on a small ragged shape; 6: 256 x 256 tiles, 7: 384 x 192, 8: 192 x 384):
@@ -449,8 +449,8 @@ def test_twenty_runs_are_bit_identical(schedule):
 @pytest.mark.parametrize("schedule", ["scratch", "twopass"])
 def test_large_shape_kernel_is_bit_repeatable_and_matches_the_register_staged_one(schedule):
     # a shape big enough for the default path to pick the direct-to-LDS kernel (1024 work items of 256 x 256):
-    # ten runs bit-identical (its loads are waited for by hand: a missed wait would show as run-to-run noise),
-    # and the same numbers as the register-staged kernel, which computes every element in the same order
+    # ten runs bit-identical (its loads and LDS reads are waited for by hand: a missed wait would show as run-to-run
+    # noise), and the same numbers as the register-staged kernel up to the order of the additions
     rng = np.random.default_rng(5)
     B, T, P, D = 4, 96, 4096, 4096
     X = W.float32_to_bf16_bits(rng.standard_normal((B, T, P)).astype(np.float32))
@@ -459,9 +459,15 @@ def test_large_shape_kernel_is_bit_repeatable_and_matches_the_register_staged_on
     for _ in range(9):
         again = run_layer(X, dY, 1.0, 0.0, 3, 2, schedule)
         assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+    assert F.flashdp_last_kernel() == "gemm_mfma_dma16_kernel"
+    # the 32x32x16 form of the direct-to-LDS kernel adds the products in the order of the register-staged kernel:
+    # the same bits; the default kernel (16x16x32: 32 products per accumulation step instead of 16) rounds
+    # differently in the last place
+    wide = run_layer(X, dY, 1.0, 0.0, 3, 2, schedule, tile=6)
     staged = run_layer(X, dY, 1.0, 0.0, 3, 2, schedule, tile=4)
-    assert np.array_equal(first[1], staged[1])
-    assert np.array_equal(first[0], staged[0]) or rel_fro(first[0], staged[0].astype(np.float64)) <= 1e-6
+    assert np.array_equal(wide[1], staged[1])
+    assert np.array_equal(wide[0], staged[0]) or rel_fro(wide[0], staged[0].astype(np.float64)) <= 1e-6
+    assert np.allclose(first[1], staged[1], rtol=1e-6, atol=0) and rel_fro(first[0], staged[0].astype(np.float64)) <= 2e-6
     want, wn = O.linear_dp_grad(X, dY, 1.0, 0.0, 3, 2)
     assert np.max(np.abs(first[1] - wn) / wn) <= 1e-4
     assert rel_fro(first[0], want) <= tight_tol("bf16", schedule)
@@ -474,10 +480,11 @@ def _random_shapes(n, seed):
 
 
 @pytest.mark.parametrize("shape", _random_shapes(12, 2024))
-@pytest.mark.parametrize("tile", [4, 6, 7, 8])
+@pytest.mark.parametrize("tile", [4, 6, 7, 8, 9])
 def test_random_shapes_both_kernel_families(shape, tile):
     # seeded random (B, T, d_in, d_out) with ragged tiles in every dimension, through the register-staged and the
-    # direct-to-LDS kernels (6: 256 x 256 tiles, 7: 384 x 192, 8: 192 x 384); scratch schedule (norm + spill +
+    # direct-to-LDS kernels (6: 256 x 256 tiles, 7: 384 x 192, 8: 192 x 384, 9: 256 x 256 on the 16x16x32 instruction);
+    # scratch schedule (norm + spill +
     # aggregation) and the plain batch gradient
     B, T, P, D = shape
     base = W.WORKLOADS["gpt2_small_mlp_up"]
@@ -495,7 +502,7 @@ def test_random_shapes_both_kernel_families(shape, tile):
 @pytest.mark.parametrize("shape,kernel", [((8, 70, 768, 3072), "gemm_mfma_dma_shaped_kernel"),      # 288 items of 256 x 256, 256 of 384 x 192
                                           ((8, 70, 3072, 768), "gemm_mfma_dma_shaped_kernel"),      # the same, 192 x 384
                                           ((8, 70, 760, 3064), "gemm_mfma_dma_shaped_kernel"),      # ragged edges in both
-                                          ((8, 70, 1024, 3072), "gemm_mfma_dma_kernel")])            # 384 items either way
+                                          ((8, 70, 1024, 3072), "gemm_mfma_dma16_kernel")])            # 384 items either way
 @pytest.mark.parametrize("schedule", ["scratch", "twopass", "explicit"])
 def test_tile_shape_follows_the_number_of_rounds(shape, kernel, schedule):
     # work items of a per-sample pass are equally long: where 384 x 192 (or 192 x 384) tiles need fewer rounds of the

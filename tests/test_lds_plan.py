@@ -256,3 +256,79 @@ def test_shaped_plan_of_the_square_tile_is_the_square_plan(plan):
     for lane in range(64):
         for block in range(8):
             assert plan.sp_frag_offset(lane, block, 256) == plan.plan_frag_offset(lane, block)
+
+
+# ---- the 256 x 256 kernel on the 16x16x32 matrix-core instruction (csrc/lds_plan16.h) ----
+
+def fill_stage16(plan, stage):
+    n = plan.plan_stage_elems()
+    owner = -np.ones((STAGES * n, 3), dtype=np.int64)
+    writes = np.zeros(STAGES * n, dtype=np.int64)
+    for operand in range(2):
+        for wave in range(WAVES):
+            for q in range(2):
+                base = plan.p16_load_dst_bytes(stage, operand, wave, q)
+                for lane in range(64):
+                    row = plan.p16_load_row(wave, lane) + 16 * q
+                    chunk = plan.p16_load_chunk(wave, lane)
+                    assert 0 <= row < 32 and 0 <= chunk < 32
+                    e0 = (base + 16 * lane) // 2
+                    for e in range(8):
+                        owner[e0 + e] = (operand, row, 8 * chunk + e)
+                        writes[e0 + e] += 1
+    return owner, writes
+
+
+@pytest.mark.parametrize("stage", range(STAGES))
+def test_16x16x32_plan_loads_fill_each_stage_exactly_once(plan, stage):
+    n, op_n = plan.plan_stage_elems(), plan.plan_operand_elems()
+    owner, writes = fill_stage16(plan, stage)
+    mine = np.zeros(STAGES * n, dtype=bool)
+    for operand in range(2):                      # the ring is operand-major: 4 dY tiles, then 4 X tiles
+        b = plan.p16_tile_base(stage, operand)
+        assert b == (operand * STAGES + stage) * op_n
+        mine[b:b + op_n] = True
+    assert np.all(writes[mine] == 1) and writes.sum() == n       # this stage's two tiles, once; nothing else
+    for operand in range(2):
+        for row in range(32):
+            for col in range(256):
+                slot = plan.p16_tile_base(stage, operand) + plan.p16_kept_at(row, col)
+                assert tuple(owner[slot]) == (operand, row, col)
+    # every fragment read reaches every stage through the 16-bit offset field: stage offset + second read + k... < 64 KB
+    assert 2 * ((STAGES - 1) * op_n + 4 * plan.plan_row()) < 65536
+
+
+def test_16x16x32_plan_fragment_reads_deliver_the_operand_layout(plan):
+    """v_mfma_f32_16x16x32 wants, in lane l, operand[r = l % 16][k = 8 (l / 16) + 0..7] of the 16-wide block: k = tile
+    row inside the 32-deep k-tile, r = column inside the block.  Two transposed reads (rows f, f + 4)."""
+    ROW = plan.plan_row()
+    owner, _ = fill_stage16(plan, 3)
+    for operand in range(2):
+        for block in range(16):
+            addr = np.zeros((2, 64), dtype=np.int64)
+            for half in range(2):
+                for lane in range(64):
+                    a = plan.p16_frag_offset(lane, block) + half * 4 * ROW
+                    assert 0 <= a and a + 4 <= plan.plan_operand_elems() and (2 * a) % 8 == 0
+                    addr[half, lane] = plan.p16_tile_base(3, operand) + a
+            for lane in range(64):
+                g, i = lane // 16, lane % 16
+                for half in range(2):
+                    for j in range(4):
+                        src_lane = 16 * g + (i // 4) + 4 * j
+                        op, row, col = owner[addr[half, src_lane] + (i % 4)]
+                        assert op == operand
+                        assert row == 8 * (lane // 16) + 4 * half + j
+                        assert col == 16 * block + lane % 16
+
+
+def test_16x16x32_plan_transposed_reads_are_bank_conflict_free(plan):
+    ROW = plan.plan_row()
+    for block in range(16):
+        for half in range(2):
+            for half_wave in range(2):
+                banks = []
+                for lane in range(32 * half_wave, 32 * half_wave + 32):
+                    byte = 2 * (plan.p16_frag_offset(lane, block) + half * 4 * ROW)
+                    banks += [(byte // 4) % 64, (byte // 4 + 1) % 64]
+                assert len(set(banks)) == 64
