@@ -934,7 +934,7 @@ int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* 
 }
 
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream) {
-  if (pattern < 0 || pattern > 9 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
+  if (pattern < 0 || pattern > 11 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
     return FLASHDP_INVALID_ARGUMENT;
   int dev = 0;
   int st = device_or_error(&dev);
@@ -942,7 +942,19 @@ int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void
   if (pattern == 2 || pattern == 3 || pattern == 8) {   // zeros / random with the operand fragments re-read from LDS every k-step (8: random, 16x16x32)
     hipLaunchKernelGGL(mfma_lds_probe_kernel, dim3((unsigned)workgroups), dim3(512), lds_plan::STAGE_ELEMS * 2, static_cast<hipStream_t>(stream), pattern == 8 ? 5 : pattern - 2, iters, sink);
   } else {
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), pattern, iters, sink);
+    const dim3 g((unsigned)workgroups), b(512);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (pattern) {
+      case 0: hipLaunchKernelGGL(mfma_probe_kernel<0>, g, b, 0, s, iters, sink); break;
+      case 1: hipLaunchKernelGGL(mfma_probe_kernel<1>, g, b, 0, s, iters, sink); break;
+      case 4: hipLaunchKernelGGL(mfma_probe_kernel<4>, g, b, 0, s, iters, sink); break;
+      case 5: hipLaunchKernelGGL(mfma_probe_kernel<5>, g, b, 0, s, iters, sink); break;
+      case 6: hipLaunchKernelGGL(mfma_probe_kernel<6>, g, b, 0, s, iters, sink); break;
+      case 7: hipLaunchKernelGGL(mfma_probe_kernel<7>, g, b, 0, s, iters, sink); break;
+      case 9: hipLaunchKernelGGL(mfma_probe_kernel<9>, g, b, 0, s, iters, sink); break;
+      case 10: hipLaunchKernelGGL(mfma_probe_kernel<10>, g, b, 0, s, iters, sink); break;
+      default: hipLaunchKernelGGL(mfma_probe_kernel<11>, g, b, 0, s, iters, sink); break;
+    }
   }
   HIP_TRY(hipGetLastError());
   return FLASHDP_OK;

@@ -20,7 +20,9 @@ namespace flashdp {
 // depends on how operands are delivered or on the values themselves.  7: the values of 1 through
 // v_mfma_f32_16x16x32_bf16 (two per 32x32x16 instruction of the other patterns: the same FLOPs, half the reuse of
 // an operand element inside the instruction); 9: the same instruction on zeros (its issue-limited rate).
-__global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int iters, float* __restrict__ sink) {
+// (one instantiation per pattern: in a single kernel with a run-time switch the patterns disturbed each other's code)
+template <int pattern>
+__global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int iters, float* __restrict__ sink) {
   const uint32_t gid = blockIdx.x * 512u + threadIdx.x;
   s16x8_t fa[2][4], fb[2][2];
   auto fill = [&](s16x8_t& f, uint32_t salt) {
@@ -31,7 +33,7 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
       // sign and 7 mantissa bits from the hash, exponent of 0.5 .. 2 (pattern 6: of 2^-7 .. 2)
       const uint32_t ex = pattern == 6 ? 120u + ((h >> 16) % 8u) : 126u + ((h >> 16) % 2u);
       const uint32_t bits = (h & 0x8000u) | (ex << 7) | (h & 0x7Fu);
-      f[e] = (pattern && pattern != 9) ? (short)bits : (short)0;
+      f[e] = (pattern && pattern != 9) ? (short)bits : (short)0;   // (10, 11: random)
     }
   };
 #pragma unroll
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-  if (pattern == 4) {
+  if constexpr (pattern == 4) {
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
       for (int s = 0; s < 2; ++s)
@@ -60,7 +62,40 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
             acc[i][j] = mfma32<DT_BF16>(fb[s][j], fa[s][i], acc[i][j]);
           }
     }
-  } else if (pattern == 7 || pattern == 9) {
+  } else if constexpr (pattern == 10 || pattern == 11) {
+    // 16x16x32 on random operands with the accumulators updated in place (inline assembly), held in the
+    // accumulation registers (10) or in ordinary vector registers (11)
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    f32x4_t small[4][2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) small[i][j][h] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              if constexpr (pattern == 10) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(small[i][j][h]) : "v"(fb[s][j]), "v"(fa[s][i]));
+              else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(small[i][j][h]) : "v"(fb[s][j]), "v"(fa[s][i]));
+            }
+    }
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][e] += small[i][j][h][e];
+  } else if constexpr (pattern == 7 || pattern == 9) {
     typedef float f32x4_t __attribute__((ext_vector_type(4)));
     f32x4_t small[4][2][2];
 #pragma unroll
@@ -89,7 +124,7 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int pattern, int ite
         for (int h = 0; h < 2; ++h)
 #pragma unroll
           for (int e = 0; e < 4; ++e) acc[i][j][e] += small[i][j][h][e];
-  } else if (pattern == 5) {
+  } else if constexpr (pattern == 5) {
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
       for (int s = 0; s < 2; ++s)
