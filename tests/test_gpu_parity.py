@@ -473,6 +473,41 @@ def test_large_shape_kernel_is_bit_repeatable_and_matches_the_register_staged_on
     assert rel_fro(first[0], want) <= tight_tol("bf16", schedule)
 
 
+def _medium_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = [(1, 1, 8, 8), (2, 31, 264, 520), (1, 129, 776, 8), (3, 640, 1032, 1544)]
+    shapes += [(int(rng.integers(1, 6)), int(rng.integers(1, 700)), 8 * int(rng.integers(1, 260)), 8 * int(rng.integers(1, 260)))
+               for _ in range(n)]
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _medium_shapes(10, 77))
+def test_both_matrix_core_forms_of_the_large_tile_kernel_agree(shape):
+    # the 16x16x32 kernel (hand-written main loop, its own LDS layout) against the 32x32x16 one on shapes of up to
+    # 2000 features and 700 tokens, ragged in every dimension, through parking + aggregation and through the plain
+    # batch gradient (the batch-accumulating mode, a k-range that runs across samples): no oracle, so no size limit
+    B, T, P, D = shape
+    rng = np.random.default_rng(hash(shape) % (1 << 31))
+    X = W.float32_to_bf16_bits(rng.standard_normal((B, T, P)).astype(np.float32))
+    dY = W.float32_to_bf16_bits((rng.standard_normal((B, T, D)) * 0.02 * (10.0 ** rng.uniform(-1, 1, size=(B, 1, 1)))).astype(np.float32))
+    a = run_layer(X, dY, 1.0, 0.0, 5, 1, "scratch", tile=9)
+    b = run_layer(X, dY, 1.0, 0.0, 5, 1, "scratch", tile=6)
+    assert np.allclose(a[1], b[1], rtol=2e-6, atol=0)
+    scale = float(np.sqrt(np.mean(b[0].astype(np.float64) ** 2))) + 1e-30
+    assert np.max(np.abs(a[0].astype(np.float64) - b[0])) <= 2.0 ** -7 * float(np.max(np.abs(b[0]))) + 1e-6 * scale   # at most a last place of the parked bf16
+    assert rel_fro(a[0], b[0].astype(np.float64)) <= 1e-4
+    two = [run_layer(X, dY, 1.0, 0.0, 5, 1, "twopass", tile=t) for t in (9, 6)]
+    assert np.allclose(two[0][1], two[1][1], rtol=2e-6, atol=0) and rel_fro(two[0][0], two[1][0].astype(np.float64)) <= 2e-6
+    outs = []
+    for t in (9, 6):
+        out = torch.full((D, P), float("nan"), device=DEV)
+        with env(FLASHDP_TILE=t):
+            F.flashdp_plain_grad(to_device(X), to_device(dY), B, T, P, D, F.BF16, out)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    assert np.all(np.isfinite(outs[0])) and rel_fro(outs[0], outs[1].astype(np.float64)) <= 2e-6
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     return [(int(rng.integers(1, 6)), int(rng.integers(1, 300)), 8 * int(rng.integers(1, 76)), 8 * int(rng.integers(1, 76)))
