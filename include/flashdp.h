@@ -140,7 +140,9 @@ typedef struct flashdp_layer {
 /* Algorithm 1 for one layer with the calling thread's context (stream, dtype, layer index, schedule,
  * workspace; see the setters below; defaults: null stream, bf16, layer 0, AUTO, library-owned workspace).
  * When no workspace has been set the library allocates one with hipMalloc on first use and keeps it
- * (grow-only, per device) until flashdp_release(); allocation may synchronise the device. */
+ * (grow-only, per device, grown by at least half at a time) until flashdp_release(); growing it synchronises
+ * the device, frees and allocates: a caller that must not stall in a step sets a workspace of
+ * flashdp_workspace_bytes() itself, or uses flashdp_linear_dp_grad_static. */
 int flashdp_linear_dp_grad(const void* X, const void* dY, int64_t B, int64_t T, int64_t d_in, int64_t d_out,
                            float C, float sigma, uint64_t seed, float* out_grad, float* out_norms);
 

@@ -418,14 +418,24 @@ int owned_workspace(size_t need, void** ptr, size_t* bytes) {
   std::lock_guard<std::mutex> lock(g_ws_mutex);
   OwnedWs& w = g_owned[dev];
   if (w.bytes < need) {
+    // Growing costs a device-wide synchronisation (earlier calls may still use the old block), a free and an
+    // allocation, inside what may be a training step: grow by at least half, so that a sequence of slowly growing
+    // requests (layers met in increasing size) reallocates a few times, not every time.  A caller that must not
+    // stall passes its own workspace.
+    const size_t want = std::max(need, w.bytes + w.bytes / 2);
     if (w.ptr) {
-      if (hipDeviceSynchronize() != hipSuccess) return FLASHDP_HIP_ERROR;   // earlier calls may still use it
+      if (hipDeviceSynchronize() != hipSuccess) return FLASHDP_HIP_ERROR;
       (void)hipFree(w.ptr);
       w.ptr = nullptr; w.bytes = 0;
     }
     void* p = nullptr;
-    if (hipMalloc(&p, need) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; }
-    w.ptr = p; w.bytes = need;
+    size_t got = want;
+    if (hipMalloc(&p, want) != hipSuccess) {
+      (void)hipGetLastError();
+      got = need;
+      if (hipMalloc(&p, need) != hipSuccess) { (void)hipGetLastError(); return FLASHDP_HIP_ERROR; }
+    }
+    w.ptr = p; w.bytes = got;
   }
   *ptr = w.ptr; *bytes = w.bytes;
   return FLASHDP_OK;
