@@ -175,7 +175,7 @@ def mfma_only(F, torch, dev):
     flop = wgs * 8 * iters * 16 * 32768.0
     out = {}
     for name, pattern in (("zeros", 0), ("random", 1), ("lds_zeros", 2), ("lds_random", 3), ("random_shared_operand_order", 4),
-                          ("random_one_operand_pair", 5), ("random_wide_exponents", 6), ("random_16x16x32", 7), ("lds_random_16x16x32", 8), ("zeros_16x16x32", 9), ("random_16x16x32_acc_regs", 10), ("random_16x16x32_in_place", 11)):
+                          ("random_one_operand_pair", 5), ("random_wide_exponents", 6), ("random_16x16x32", 7), ("lds_random_16x16x32", 8), ("zeros_16x16x32", 9), ("random_16x16x32_acc_regs", 10), ("random_16x16x32_in_place", 11), ("lds_random_16x16x32_fewer_reads", 12)):
         ms = time_events(lambda: F.flashdp_mfma_probe(pattern, iters, wgs, sink), 3, 2)
         out[name + "_tflops"] = round(flop / ms / 1e9, 1)
     return out

@@ -248,7 +248,8 @@ int flashdp_set_schedule(int schedule);
  * operands are delivered, or on the values themselves?); 7 = the random operands of 1 through the 16x16x32
  * instruction, two per 32x32x16 one (the same FLOPs), 8 = the same with the LDS fragment reads of 3, 9 = 16x16x32 on
  * zeros, 10 / 11 = 16x16x32 on random operands with the accumulators updated in place, in accumulation registers /
- * in ordinary vector registers.  `workgroups` workgroups of 8 waves, each wave issuing 16 * iters instructions of
+ * in ordinary vector registers, 12 = pattern 8 with a third fewer fragment reads (what 128 x 128 per wave would
+ * save).  `workgroups` workgroups of 8 waves, each wave issuing 16 * iters instructions of
  * 32768 FLOP (32 * iters of 16384 for the 16x16x32 patterns); sink (device, 4 bytes) is never written in practice.
  * INVALID_ARGUMENT for other patterns, iters or workgroups <= 0 or absurdly large, or a null sink. */
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream);

@@ -944,13 +944,19 @@ int flashdp_box_muller(const uint32_t* words, int64_t n_groups, float* z, void* 
 }
 
 int flashdp_mfma_probe(int pattern, int iters, int workgroups, float* sink, void* stream) {
-  if (pattern < 0 || pattern > 11 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
+  if (pattern < 0 || pattern > 12 || iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20) || !sink)
     return FLASHDP_INVALID_ARGUMENT;
   int dev = 0;
   int st = device_or_error(&dev);
   if (st != FLASHDP_OK) return st;
-  if (pattern == 2 || pattern == 3 || pattern == 8) {   // zeros / random with the operand fragments re-read from LDS every k-step (8: random, 16x16x32)
-    hipLaunchKernelGGL(mfma_lds_probe_kernel, dim3((unsigned)workgroups), dim3(512), lds_plan::STAGE_ELEMS * 2, static_cast<hipStream_t>(stream), pattern == 8 ? 5 : pattern - 2, iters, sink);
+  if (pattern == 2 || pattern == 3 || pattern == 8 || pattern == 12) {   // the operand fragments re-read from LDS every k-step
+    const dim3 g((unsigned)workgroups), b(512);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t lds_bytes = lds_plan::STAGE_ELEMS * 2;
+    if (pattern == 2) hipLaunchKernelGGL((mfma_lds_probe_kernel<false, 0>), g, b, lds_bytes, s, iters, sink);
+    else if (pattern == 3) hipLaunchKernelGGL((mfma_lds_probe_kernel<true, 0>), g, b, lds_bytes, s, iters, sink);
+    else if (pattern == 8) hipLaunchKernelGGL((mfma_lds_probe_kernel<true, 1>), g, b, lds_bytes, s, iters, sink);
+    else hipLaunchKernelGGL((mfma_lds_probe_kernel<true, 2>), g, b, lds_bytes, s, iters, sink);
   } else {
     const dim3 g((unsigned)workgroups), b(512);
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -156,7 +156,11 @@ __global__ __launch_bounds__(512, 2) void mfma_probe_kernel(int iters, float* __
 // The same instruction mix with the operand fragments coming from LDS through the transposed reads of the
 // contraction kernel (a 32 KB stage filled once with zeros or pseudo-random values, re-read every k-tile):
 // matrix cores + LDS traffic, still no memory loads and no barrier in the loop.
-__global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int iters, float* __restrict__ sink) {
+// RANDOM: pseudo-random instead of zero operands.  FORM 0: 32x32x16; 1: 16x16x32 (two per 32x32x16 instruction);
+// 2: 16x16x32 with a third fewer fragment reads (the X fragments are read once, not every k-step): what a tiling with
+// 128 x 128 per wave would save in LDS traffic.
+template <bool RANDOM, int FORM>
+__global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int iters, float* __restrict__ sink) {
   extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave % 2, wave_n = wave / 2;
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
     uint32_t h = ((uint32_t)e * 0x9E3779B9u) ^ (blockIdx.x * 0x85EBCA6Bu);
     h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 12; h *= 0x297A2D39u; h ^= h >> 15;
     const uint32_t bits = (h & 0x8000u) | ((126u + ((h >> 16) % 2u)) << 7) | (h & 0x7Fu);
-    lds[e] = (pattern & 1) ? (unsigned short)bits : (unsigned short)0;
+    lds[e] = RANDOM ? (unsigned short)bits : (unsigned short)0;
   }
   __syncthreads();
   int a_rd[4], b_rd[2];
@@ -188,6 +192,15 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
       pfb[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
   };
+  auto load_a_frags = [&](int ks, s16x8_t* pfa) {
+    const unsigned short* base = lds + ks * 16 * lds_plan::ROW;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const s16x4_t lo = lds_read_tr(base + a_rd[i]);
+      const s16x4_t hi = lds_read_tr(base + a_rd[i] + 4 * lds_plan::ROW);
+      pfa[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+  };
   f32x16_t acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -196,7 +209,8 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
   load_frags(0, fa[0], fb[0]);
-  if (pattern & 4) {   // the same fragment traffic feeding 16x16x32 instructions, two per 32x32x16 one
+  load_frags(1, fa[1], fb[1]);
+  if constexpr (FORM != 0) {   // the same fragment traffic feeding 16x16x32 instructions, two per 32x32x16 one
     typedef float f32x4_t __attribute__((ext_vector_type(4)));
     f32x4_t small[4][2][2];
 #pragma unroll
@@ -208,7 +222,7 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
     for (int it = 0; it < iters; ++it) {
       static_for<2>([&](auto ks_c) {
         constexpr int ks = decltype(ks_c)::value;
-        load_frags(ks ^ 1, fa[ks ^ 1], fb[ks ^ 1]);
+        if constexpr (FORM == 2) load_a_frags(ks ^ 1, fa[ks ^ 1]); else load_frags(ks ^ 1, fa[ks ^ 1], fb[ks ^ 1]);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -217,7 +231,7 @@ __global__ __launch_bounds__(512, 2) void mfma_lds_probe_kernel(int pattern, int
             for (int h = 0; h < 2; ++h)
               small[i][j][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fb[ks][j]), __builtin_bit_cast(bf16x8_t, fa[ks][i]),
                                                                        small[i][j][h], 0, 0, 0);
-        sched_interleave<0, 16, 12, 0, 0>();
+        sched_interleave<0, 16, FORM == 2 ? 8 : 12, 0, 0>();
       });
     }
 #pragma unroll
