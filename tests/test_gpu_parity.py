@@ -506,7 +506,7 @@ def test_both_matrix_core_forms_of_the_large_tile_kernel_agree(shape):
             F.flashdp_plain_grad(to_device(X), to_device(dY), B, T, P, D, F.BF16, out)
         torch.cuda.synchronize()
         outs.append(out.cpu().numpy())
-    assert np.all(np.isfinite(outs[0])) and rel_fro(outs[0], outs[1].astype(np.float64)) <= 2e-6
+    assert np.all(np.isfinite(outs[0])) and np.array_equal(outs[0], outs[1])     # the contraction itself: bit for bit
 
 
 def _random_shapes(n, seed):
